@@ -1,0 +1,433 @@
+"""Pins for the CPU oracle's allocator, lane assignment and scheduler.
+
+None of these tests compares the oracle with itself: each one checks it against
+numbers worked by hand from the paper (tests/golden), against the safety
+condition, or against an independent brute-force model written here.
+"""
+import itertools
+import os
+import random
+
+import numpy as np
+import pytest
+
+from oracle import pool as op
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+MiB, GB = 1 << 20, 10 ** 9
+
+
+def rows(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return [[int(x) for x in ln.split()] for ln in f if ln.strip() and ln[0] != '#']
+
+
+# ------------------------------------------------------------------ worked examples
+def test_deadlock_example_shares_one_lane():
+    (C, P, E, la, lb, nl), = rows("deadlock_example.txt")
+    p = op.Pool(C * GB, granule=1000)
+    sa, a = p.job_arrive(P * GB, E * GB)
+    sb, b = p.job_arrive(P * GB, E * GB)
+    assert (sa, sb) == (op.OK, op.OK)
+    assert (p.jobs[a].lane, p.jobs[b].lane, len(p.lanes)) == (la, lb, nl)
+    p.check_invariants()
+    # serialized: a round runs exactly one of them
+    p.set_pending(a, 5), p.set_pending(b, 5)
+    assert all(len(p.schedule_iteration()) == 1 for _ in range(4))
+
+
+def test_workload1_layout_matches_hand_trace():
+    p = op.Pool(4 * MiB, granule=256, policy=op.RR)
+    for _ in range(4):
+        st, _ = p.job_arrive(512 * 1024, MiB, 0, 8)
+        assert st == op.OK
+    for job, lane, base, size, off in rows("workload1_layout.txt"):
+        j = p.jobs[job]
+        assert (j.lane, p.lane_base(j.lane), p.lane_by_id(j.lane).size, j.off) == \
+               (lane, base, size, off)
+    # round-robin inside each lane: rounds alternate {0,1} and {2,3}
+    seq = [p.schedule_iteration() for _ in range(16)]
+    assert seq == [[(0, 0), (1, 1)], [(2, 0), (3, 1)]] * 8
+    assert all(j.pending == 0 and j.served == 8 for j in p.jobs)
+    assert p.schedule_iteration() == []
+
+
+def test_never_fits_and_queueing():
+    p = op.Pool(1000, granule=10)
+    assert p.job_arrive(600, 500)[0] == op.ENEVER          # cannot run even alone
+    assert p.job_arrive(0, 10)[0] == op.EINVAL
+    assert p.job_arrive(300, 300)[0] == op.OK               # lane 0
+    st, q = p.job_arrive(300, 600)                          # 300+300 + 600 > 1000 in any branch
+    assert st == op.IS_QUEUED and p.Q == [q]
+    p.check_invariants()
+    assert p.job_finish(0) == op.OK                         # lane 0 goes away -> queue retried
+    assert p.jobs[q].state == op.RESIDENT and p.Q == []
+    p.check_invariants()
+
+
+def test_findlane_prefers_new_then_best_match_then_grow():
+    p = op.Pool(100, granule=1)
+    _, a = p.job_arrive(5, 30)          # new lane 0 (30)
+    _, b = p.job_arrive(5, 20)          # new lane 1 (20): 10+50 <= 100
+    assert [l.size for l in p.lanes] == [30, 20]
+    _, c = p.job_arrive(5, 18)          # new lane 2 (18): 15 + 68 = 83
+    _, d = p.job_arrive(5, 19)          # new would be 20+68+19 = 107 > 100 -> best match
+    assert p.jobs[d].lane == 1          # slack 1 in lane 1 (20) beats slack 11 in lane 0
+    _, e = p.job_arrive(2, 25)          # 22+68 = 90: fits lane 0 only
+    assert p.jobs[e].lane == 0
+    _, f = p.job_arrive(1, 31)          # nothing fits 31; grow smallest lane first:
+    # lane 2 (18) -> 23 + 68 - 18 + 31 = 104 > 100; lane 1 (20) -> 102 > 100; lane 0 (30) -> 92
+    assert p.jobs[f].lane == 0 and p.lane_by_id(0).size == 31
+    p.check_invariants()
+
+
+def test_grow_picks_smallest_feasible_lane():
+    p = op.Pool(100, granule=1)
+    p.job_arrive(10, 20)
+    p.job_arrive(10, 30)
+    _, c = p.job_arrive(10, 35)         # new: 30+50+35 = 115; no lane >= 35; grow lane 0: 30+50-20+35 = 95
+    assert p.jobs[c].lane == 0 and [l.size for l in p.lanes] == [35, 30]
+    p.check_invariants()
+
+
+def test_best_match_tie_goes_to_lane_with_fewer_jobs_then_oldest():
+    p = op.Pool(64, granule=1, max_lanes=2)
+    for _ in range(2):
+        p.job_arrive(1, 10)
+    assert [p.job_arrive(1, 10)[1] for _ in range(3)] == [2, 3, 4]
+    assert [p.jobs[i].lane for i in range(5)] == [0, 1, 0, 1, 0]
+
+
+def test_lane_lives_until_last_job_leaves_and_neighbours_slide_for_free():
+    mem = np.zeros(100, np.uint8)
+    p = op.Pool(100, granule=1, mem=mem, max_lanes=3)
+    _, a = p.job_arrive(5, 20)          # lane 0 = [80,100)
+    _, b = p.job_arrive(5, 10)          # lane 1 = [70,80)
+    _, c = p.job_arrive(5, 20)          # lane 2 = [50,70)
+    _, d = p.job_arrive(5, 20)          # three lanes is the cap -> shares lane 0 or 2 (slack 0, one job each): oldest
+    assert p.jobs[d].lane == 0 and p.lane_by_id(0).ref == 2
+    assert [p.lane_base(i) for i in (0, 1, 2)] == [80, 70, 50]
+    p.job_finish(a)
+    assert len(p.lanes) == 3            # d still holds lane 0
+    p.job_finish(b)                     # lane 1 disappears, lane 2 slides up by 10
+    assert [l.id for l in p.lanes] == [0, 2] and p.lane_base(2) == 60
+    assert p.stats['bytes_d2d'] == 0 and p.stats['moves'] == 0     # nothing was copied
+    assert p.stats['lanes_deleted'] == 1 and p.stats['lanes_moved'] == 1
+    p.check_invariants()
+
+
+def test_queued_job_admitted_when_a_lane_disappears():
+    p = op.Pool(100, granule=1)
+    _, a = p.job_arrive(10, 40)
+    _, b = p.job_arrive(10, 30)
+    st, c = p.job_arrive(30, 35)        # new 50+70+35; use lane0: 50+70=120 > 100; queued
+    assert st == op.IS_QUEUED
+    p.job_finish(b)                     # lane 1 gone: 40 + 40 + 35 > 100, lane 0: 40+40 <= 100
+    assert p.jobs[c].state == op.RESIDENT and p.jobs[c].lane == 0
+    p.check_invariants()
+
+
+# ------------------------------------------------------------------ brute force
+def independent_feasible(C, A, max_lanes, resident_P, lanes, P, E):
+    """Is there ANY single action (open / join / grow one lane) after which the
+    safety condition  sum P + sum L <= C,  L >= E  holds?  Written directly from
+    the safety condition, not from FindLane."""
+    SP = sum(resident_P) + P
+    if (max_lanes == 0 or len(lanes) < max_lanes) and SP + sum(lanes) + E <= C:
+        return True
+    for i, L in enumerate(lanes):
+        newL = max(L, E)
+        if SP + sum(lanes) - L + newL <= C:
+            return True
+    return False
+
+
+def interleavings(n):
+    """All event orders of n jobs: arrivals in job order, each finish after its arrival."""
+    def rec(seq, arrived, finished):
+        if len(seq) == 2 * n:
+            yield list(seq)
+            return
+        if arrived < n:
+            yield from rec(seq + ["a"], arrived + 1, finished)
+        for j in range(arrived):
+            if j not in finished:
+                yield from rec(seq + [j], arrived, finished | {j})
+    return rec([], 0, frozenset())
+
+
+@pytest.mark.parametrize("max_lanes", [0, 2])
+def test_bruteforce_tiny_pools(max_lanes):
+    """Pool of 16 granules: every (P, E) combination of three jobs from a small
+    set, under every arrive/finish interleaving, plus four-job scripts."""
+    C, A = 16, 1
+    sizes = [(1, 2), (2, 5), (3, 3), (1, 8), (4, 7), (6, 9)]
+    scripts3 = list(interleavings(3))
+    assert len(scripts3) == 15       # 6! / (2^3 * 3!)
+    scripts4 = [["a", "a", "a", "a", 0, 2, 1, 3], ["a", "a", 0, "a", "a", 1, 3, 2],
+                ["a", "a", "a", 1, "a", 0, 3, 2], ["a", 0, "a", "a", 2, "a", 1, 3]]
+    cases = [(c, s) for c in itertools.product(range(len(sizes)), repeat=3) for s in scripts3]
+    cases += [(c, s) for c in itertools.product(range(len(sizes)), repeat=4) for s in scripts4]
+    checked = 0
+    for combo, script in cases:
+        p = op.Pool(C, granule=A, max_lanes=max_lanes, policy=op.PACK,
+                    mem=np.zeros(C, np.uint8))
+        content, nxt = {}, 0
+        for ev in script:
+            if ev == "a":
+                P, E = sizes[combo[nxt]]
+                nxt += 1
+                p.job_arrive(P, E, 0, 3)
+            else:
+                p.job_finish(ev)
+                content.pop(ev, None)
+            # give newly admitted jobs recognisable bytes
+            for j in p.jobs:
+                if j.state == op.RESIDENT and j.id not in content:
+                    content[j.id] = np.full(j.P, 10 + j.id, np.uint8)
+                    p.mem[j.off:j.off + j.P] = content[j.id]
+            p.check_invariants()
+            # persistent bytes survive whatever compaction happened
+            for j in p.jobs:
+                if j.state == op.RESIDENT:
+                    assert (p.mem[j.off:j.off + j.P] == content[j.id]).all()
+            # nobody waits while a feasible action exists
+            for q in p.Q:
+                j = p.jobs[q]
+                assert not independent_feasible(
+                    C, A, max_lanes, [r.P for r in p.resident()],
+                    [l.size for l in p.lanes], j.P, j.E)
+            checked += 1
+    assert checked > 50000
+
+
+def test_random_event_sequences_keep_invariants_and_bytes():
+    for seed in range(30):
+        rnd = random.Random(seed)
+        C = 4096
+        p = op.Pool(C, granule=16, max_lanes=rnd.choice([0, 3, 6]),
+                    policy=rnd.choice([op.RR, op.PACK, op.PRIORITY, op.FIFO]),
+                    mem=np.zeros(C, np.uint8))
+        content = {}
+        for step in range(200):
+            r = rnd.random()
+            alive = [j.id for j in p.jobs if j.state != op.DONE]
+            if r < 0.45 or not alive:
+                p.job_arrive(rnd.randint(1, 700), rnd.randint(1, 900), rnd.randint(0, 3),
+                             rnd.randint(1, 20))
+            elif r < 0.8:
+                jid = rnd.choice(alive)
+                p.job_finish(jid)
+                content.pop(jid, None)
+            elif r < 0.9:
+                p.schedule_iteration()
+            else:
+                jid = rnd.choice(alive)
+                if p.jobs[jid].state == op.RESIDENT:
+                    assert p.switch_out(jid) == op.OK
+                elif p.jobs[jid].state == op.EVICTED:
+                    assert p.switch_in(jid) in (op.OK, op.ENOMEM)
+            for j in p.jobs:
+                if j.state == op.RESIDENT and j.id not in content:
+                    content[j.id] = np.frombuffer(random.Random(seed * 1000 + j.id)
+                                                  .randbytes(j.P), np.uint8).copy()
+                    p.mem[j.off:j.off + j.P] = content[j.id]
+            p.check_invariants()
+            for j in p.jobs:
+                if j.state == op.RESIDENT:
+                    assert (p.mem[j.off:j.off + j.P] == content[j.id]).all(), (seed, step, j.id)
+
+
+# ------------------------------------------------------------------ compaction
+def test_compaction_closed_form_and_idempotent():
+    C = 1000
+    mem = np.arange(C, dtype=np.uint32).astype(np.uint8)
+    p = op.Pool(C, granule=10, mem=mem, max_lanes=1)
+    ids = [p.job_arrive(s, 50)[1] for s in (95, 41, 200, 7, 120)]   # rounded 100,50,200,10,120
+    assert [p.jobs[i].off for i in ids] == [0, 100, 150, 350, 360]
+    for i in ids:
+        j = p.jobs[i]
+        mem[j.off:j.off + j.P] = 100 + i
+    p.job_finish(ids[1])
+    p.job_finish(ids[3])
+    before = {i: mem[p.jobs[i].off:p.jobs[i].off + p.jobs[i].P].copy() for i in (0, 2, 4)}
+    plan = p.compact()
+    # exclusive prefix sum of rounded sizes 100, 200, 120; block 0 does not move
+    assert plan == [(150, 100, 200), (360, 300, 120)]
+    assert [p.jobs[i].off for i in (0, 2, 4)] == [0, 100, 300]
+    for i in (0, 2, 4):
+        j = p.jobs[i]
+        assert (mem[j.off:j.off + j.P] == before[i]).all()
+    assert p.holes(p.floor()) == [(420, p.floor() - 420)]          # a single free range
+    assert p.compact() == []                                        # idempotent
+    assert p.stats['bytes_d2d'] == 320 and p.stats['moves'] == 2
+
+
+def test_compaction_with_overlapping_source_and_destination():
+    C = 64
+    mem = np.zeros(C, np.uint8)
+    p = op.Pool(C, granule=1, mem=mem, max_lanes=1)
+    a = p.job_arrive(2, 4)[1]
+    b = p.job_arrive(40, 4)[1]
+    mem[2:42] = np.arange(1, 41)
+    p.job_finish(a)
+    assert p.compact() == [(2, 0, 40)]       # shift (2) far smaller than the block (40)
+    assert (mem[0:40] == np.arange(1, 41)).all()
+
+
+def test_allocation_triggers_compaction_only_when_fragmented():
+    p = op.Pool(100, granule=1, max_lanes=1, mem=np.zeros(100, np.uint8))
+    a = p.job_arrive(20, 10)[1]
+    b = p.job_arrive(20, 10)[1]
+    c = p.job_arrive(20, 10)[1]
+    p.job_finish(a)
+    p.job_finish(c)                          # free: [0,20) and [40,90)
+    assert p.stats['compactions'] == 0
+    d = p.job_arrive(45, 10)[1]              # fits the upper hole: no compaction
+    assert p.jobs[d].off == 40 and p.stats['compactions'] == 0
+    p.job_finish(d)
+    e = p.job_arrive(60, 10)[1]              # 70 free in total, largest hole 50 -> compaction
+    assert p.stats['compactions'] == 1 and p.jobs[b].off == 0 and p.jobs[e].off == 20
+
+
+def test_new_lane_pushes_persistent_blocks_below_the_new_floor():
+    p = op.Pool(100, granule=1, mem=np.zeros(100, np.uint8))
+    a = p.job_arrive(30, 10)[1]              # lane 0 = [90,100), block [0,30)
+    b = p.job_arrive(30, 10)[1]              # lane 1 = [80,90),  block [30,60)
+    p.mem[30:60] = 7
+    p.job_finish(a)                          # lane 0 gone; lane 1 = [90,100); hole [0,30)
+    c = p.job_arrive(10, 50)[1]              # new lane [40,90): block b reaches 60 > 40 -> compact first
+    assert p.jobs[b].off == 0 and p.jobs[c].off == 30 and (p.mem[0:30] == 7).all()
+    p.check_invariants()
+
+
+# ------------------------------------------------------------------ switching
+def test_switch_out_in_is_byte_exact_and_first_fit():
+    C = 4 * 1024
+    mem = np.zeros(C, np.uint8)
+    p = op.Pool(C, granule=256, mem=mem, max_lanes=1)
+    ids = [p.job_arrive(512, 256)[1] for _ in range(4)]
+    rng = np.random.default_rng(0)
+    data = {i: rng.integers(0, 256, 512, dtype=np.uint8) for i in ids}
+    for i in ids:
+        mem[p.jobs[i].off:p.jobs[i].off + 512] = data[i]
+    assert p.switch_out(2) == op.OK and p.jobs[2].state == op.EVICTED
+    assert p.switch_out(2) == op.ENOTRESIDENT
+    mem[1024:1536] = 0xEE                     # the freed bytes may be reused by anyone
+    assert p.switch_in(2) == op.OK and p.jobs[2].off == 1024     # same hole again
+    for i in ids:
+        assert (mem[p.jobs[i].off:p.jobs[i].off + 512] == data[i]).all()
+    assert p.stats['bytes_d2h'] == 512 and p.stats['bytes_h2d'] == 512
+
+
+def test_priority_admission_evicts_and_restores():
+    """Scaled-down preemption scenario: a long low-priority job with a large
+    persistent state and a short urgent job that does not fit beside it."""
+    C = 23 * 1024
+    mem = np.zeros(C, np.uint8)
+    p = op.Pool(C, granule=256, policy=op.PRIORITY, mem=mem)
+    _, low = p.job_arrive(20 * 1024, 2 * 1024, priority=0, pending=10 ** 6)
+    state = np.random.default_rng(3).integers(0, 256, 20 * 1024, dtype=np.uint8)
+    mem[0:20 * 1024] = state
+    st, high = p.job_arrive(2 * 1024, 2 * 1024, priority=5, pending=10)
+    assert st == op.OK
+    assert p.jobs[low].state == op.EVICTED and p.jobs[low].auto_evicted
+    mem[:] = 0x55                                                   # urgent job scribbles anywhere
+    assert [j for j, _ in p.schedule_iteration()] == [high]         # the evicted job cannot run
+    p.check_invariants()
+    p.job_finish(high)
+    assert p.jobs[low].state == op.RESIDENT
+    off = p.jobs[low].off
+    assert (mem[off:off + 20 * 1024] == state).all()
+    assert p.stats['bytes_d2h'] == 20 * 1024 == p.stats['bytes_h2d']
+    # an equal-priority arrival never evicts
+    st, same = p.job_arrive(2 * 1024, 2 * 1024, priority=0, pending=1)
+    assert st == op.IS_QUEUED and p.jobs[low].state == op.RESIDENT
+
+
+def test_priority_eviction_is_skipped_when_it_cannot_help():
+    p = op.Pool(100, granule=1, policy=op.PRIORITY)
+    _, a = p.job_arrive(10, 60, priority=0, pending=5)
+    st, b = p.job_arrive(50, 45, priority=9, pending=5)   # even alone beside lane 0 (60): 50+60 > 100
+    assert st == op.IS_QUEUED and p.jobs[a].state == op.RESIDENT and p.stats['evictions'] == 0
+
+
+# ------------------------------------------------------------------ scheduling
+def test_fair_share_follows_arrivals_and_departures():
+    """Section 5.1.2, fair sharing: with n equal jobs in one lane each gets 1/n of
+    the iterations, and the share changes right when a job arrives or leaves."""
+    p = op.Pool(1000, granule=1, max_lanes=1, policy=op.RR)
+    ran = []
+
+    def run(rounds):
+        out = []
+        for _ in range(rounds):
+            (j, _), = p.schedule_iteration()
+            out.append(j)
+        ran.extend(out)
+        return out
+    a = p.job_arrive(10, 100, 0, 10 ** 6)[1]
+    assert run(6) == [a] * 6
+    b = p.job_arrive(10, 100, 0, 10 ** 6)[1]
+    p.jobs[b].served = p.jobs[a].served       # a newcomer starts level with the lane (no catch-up burst)
+    got = run(6)
+    assert got.count(a) == 3 and got.count(b) == 3
+    c = p.job_arrive(10, 100, 0, 10 ** 6)[1]
+    p.jobs[c].served = p.jobs[a].served
+    got = run(9)
+    assert [got.count(x) for x in (a, b, c)] == [3, 3, 3]
+    p.job_finish(c)
+    got = run(6)
+    assert got.count(a) == 3 and got.count(b) == 3
+    p.job_finish(b)
+    assert run(4) == [a] * 4
+
+
+def test_fair_strict_rotation_for_equal_jobs():
+    p = op.Pool(1000, granule=1, max_lanes=1, policy=op.RR)
+    ids = [p.job_arrive(10, 100, 0, 100)[1] for _ in range(3)]
+    seq = [p.schedule_iteration()[0][0] for _ in range(9)]
+    assert seq == ids * 3
+
+
+def test_srtf_order_relations():
+    """Section 5.1.2, SRTF trace: a newly arrived shorter job stops the long
+    background job at once; of two waiting jobs the shorter runs first even if
+    it came later; a still shorter arrival preempts the running one; the
+    background job runs only when nothing shorter exists."""
+    p = op.Pool(10000, granule=1, max_lanes=1, policy=op.PRIORITY)
+    j0 = p.job_arrive(10, 100, 0, 1000)[1]
+    run = lambda: p.schedule_iteration()[0][0]
+    assert [run() for _ in range(3)] == [j0] * 3
+    j1 = p.job_arrive(10, 100, 0, 4)[1]
+    assert run() == j1                         # background job stopped immediately
+    j2 = p.job_arrive(10, 100, 0, 20)[1]       # arrives before j3 ...
+    j3 = p.job_arrive(10, 100, 0, 6)[1]        # ... but j3 is shorter
+    order = [run() for _ in range(3 + 6)]
+    assert order == [j1] * 3 + [j3] * 6
+    j4 = j2
+    assert [run() for _ in range(5)] == [j4] * 5
+    j5 = p.job_arrive(10, 100, 0, 3)[1]        # shorter than what is left of j4 (15)
+    assert [run() for _ in range(3)] == [j5] * 3
+    assert [run() for _ in range(15)] == [j4] * 15
+    assert run() == j0                         # only now the background job
+
+
+def test_priority_beats_remaining_time():
+    p = op.Pool(10000, granule=1, max_lanes=1, policy=op.PRIORITY)
+    a = p.job_arrive(10, 100, priority=1, pending=100)[1]
+    b = p.job_arrive(10, 100, priority=0, pending=2)[1]
+    assert [p.schedule_iteration()[0][0] for _ in range(3)] == [a, a, a]
+
+
+def test_pack_runs_every_lane_and_fifo_runs_one_job():
+    p = op.Pool(1000, granule=1, policy=op.PACK)
+    ids = [p.job_arrive(10, 50, 0, 2)[1] for _ in range(5)]
+    assert len(p.lanes) == 5
+    assert p.schedule_iteration() == [(i, i) for i in ids]
+    p.set_pending(ids[2], 0)                   # a model with no request is skipped
+    assert [j for j, _ in p.schedule_iteration()] == [0, 1, 3, 4]
+    q = op.Pool(1000, granule=1, policy=op.FIFO)
+    ids = [q.job_arrive(10, 50, 0, 2)[1] for _ in range(3)]
+    assert [q.schedule_iteration() for _ in range(7)] == \
+        [[(0, 0)], [(0, 0)], [(1, 1)], [(1, 1)], [(2, 2)], [(2, 2)], []]
