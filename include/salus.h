@@ -1,0 +1,238 @@
+/* salus.h - C ABI of the MI355X packed-iteration and job-switch library.
+ *
+ * One pool object manages one caller-owned range of device memory on one GPU
+ * the way Salus (arXiv 1902.04610) manages a GPU: persistent memory of every
+ * admitted job stays resident (Section 3.2.1), ephemeral memory lives in lanes
+ * (Section 3.3), jobs are admitted by the lane-assignment algorithm
+ * (Algorithm 1) under the safety condition (Section 3.3.2), and iterations are
+ * scheduled at iteration granularity (Sections 3.2.2 and 4).  On top of that
+ * model the library executes the dense layers of all jobs scheduled in a round
+ * as one grouped GEMM launch per layer depth, and moves persistent state
+ * (evict / restore to pinned host memory, on-device compaction).
+ *
+ * Conventions
+ *  - Every call returns an int32_t status: SALUS_OK, SALUS_QUEUED or a negative
+ *    error.  After an error salus_last_error() gives a message.
+ *  - "device pointer" = address valid on the GPU; "host pointer" = ordinary
+ *    process memory.  All sizes and offsets are bytes (uint64_t); offsets are
+ *    relative to the pool base.
+ *  - The library never allocates device memory.  It owns its metadata and the
+ *    pinned host buffers that hold evicted state (unless the caller passes one).
+ *  - Not thread safe: one scheduler thread drives a pool (the paper's execution
+ *    service is a singleton, Section 3.1).
+ *  - Calls that change the layout (lane_alloc, lane_free, switch_out, switch_in,
+ *    compact) are only legal between iterations: all ephemeral memory is dead
+ *    there (Section 3.2.2), and the caller must not have work in flight on
+ *    other streams that touches the pool.
+ *  - Job ids are dense, starting at 0, in arrival order.  Lane ids are dense in
+ *    creation order and never reused.
+ */
+#ifndef SALUS_H
+#define SALUS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct salus_pool salus_pool_t;
+
+enum {
+    SALUS_OK = 0,
+    SALUS_QUEUED = 1,          /* request accepted, waiting in the pending queue Q */
+    SALUS_EINVAL = -1,         /* bad argument / bad job id / wrong job state */
+    SALUS_ENOMEM = -2,         /* safety condition would be violated */
+    SALUS_ENOTRESIDENT = -3,   /* job's persistent state is not on the device */
+    SALUS_EBUSY = -4,          /* two jobs of one lane in the same launch */
+    SALUS_ENEVER = -5,         /* P + E > C: the job could not run even alone (Section 4.2) */
+    SALUS_EHIP = -6            /* the HIP runtime reported an error */
+};
+
+/* Scheduling policies of Section 4. */
+enum {
+    SALUS_POLICY_FIFO = 0,     /* oldest runnable job of the pool only */
+    SALUS_POLICY_FAIR = 1,     /* per lane: least attained service (round-robin) */
+    SALUS_POLICY_PRIORITY = 2, /* per lane: highest priority, then shortest remaining (SRTF) */
+    SALUS_POLICY_PACK = 3      /* every lane runs its oldest runnable job */
+};
+
+enum { SALUS_JOB_QUEUED = 0, SALUS_JOB_RESIDENT = 1, SALUS_JOB_EVICTED = 2, SALUS_JOB_DONE = 3 };
+
+enum { SALUS_ACT_NONE = 0, SALUS_ACT_RELU = 1, SALUS_ACT_GELU = 2 };
+
+enum { SALUS_F32 = 0, SALUS_BF16 = 1 };
+
+/* How switch_out / switch_in cross the host link. */
+enum { SALUS_COPY_KERNEL = 0,  /* the library's own copy kernel on mapped pinned memory */
+       SALUS_COPY_DMA = 1 };   /* hipMemcpyAsync (copy engine) */
+
+typedef struct {
+    uint64_t granule;      /* P and E are rounded up to it; power of two >= 16; 0 = 256 */
+    uint32_t max_lanes;    /* cap on the number of lanes; 0 = unlimited */
+    int32_t  policy;       /* SALUS_POLICY_* */
+    void    *stream;       /* hipStream_t for copies and compaction; NULL = default stream */
+    int32_t  copy_engine;  /* SALUS_COPY_* */
+    int32_t  reserved;
+} salus_config;
+
+typedef struct {
+    int32_t  state;        /* SALUS_JOB_* */
+    int32_t  lane;         /* lane id, -1 while queued */
+    int32_t  priority;
+    int32_t  auto_evicted; /* 1 if priority admission evicted it (it is restored automatically) */
+    uint64_t P, E;         /* granule-rounded sizes */
+    uint64_t persist_off;  /* valid while RESIDENT; changes on compact / switch_in */
+    uint64_t lane_off;     /* current base of the job's lane; changes when older lanes vanish or grow */
+    uint64_t lane_size;    /* L_j */
+    uint64_t pending;      /* iterations still to run */
+    uint64_t served;       /* iterations issued so far */
+    uint64_t arrival_round, admit_round;   /* admit_round = UINT64_MAX while queued */
+} salus_job_info;
+
+typedef struct { int32_t job, lane; } salus_slot;
+
+typedef struct { uint64_t src, dst, len; } salus_move;
+
+/* One layer: H_out[M x N] = act(H_in[M x K] . W[K x N]); W row-major at
+ * w_off bytes inside the job's persistent block. */
+typedef struct {
+    uint32_t K, N;
+    uint64_t w_off;
+    int32_t  act;          /* SALUS_ACT_* */
+    int32_t  reserved;
+} salus_layer;
+
+/* One job's forward pass in a packed iteration.  All three offsets are inside
+ * the job's lane (its ephemeral memory).  x: input, M x K_0, in `dtype`.
+ * y: output of the last layer, M x N_last, always float.  h: room for the
+ * intermediate activations, 2 * M * max_l(N_l) elements of `dtype` (unused
+ * with a single layer).  SALUS_BF16: weights, input and intermediate
+ * activations are bf16 (activations rounded to nearest-even), sums in float. */
+typedef struct {
+    int32_t  job;
+    uint32_t M;
+    uint32_t n_layers;
+    int32_t  dtype;        /* SALUS_F32 or SALUS_BF16 */
+    const salus_layer *layers;   /* host pointer, n_layers entries */
+    uint64_t x_off, y_off, h_off;
+} salus_gemm_desc;
+
+typedef struct {
+    uint64_t rounds, iterations;
+    uint64_t bytes_d2h, bytes_h2d, bytes_d2d;
+    uint64_t moves, compactions;
+    uint64_t lanes_opened, lanes_deleted, lanes_moved;
+    uint64_t evictions, restores, admitted, queued;
+    uint64_t gemm_launches;
+} salus_stats;
+
+enum { SALUS_EV_ADMIT = 0, SALUS_EV_EVICT = 1, SALUS_EV_RESTORE = 2, SALUS_EV_LANE_NEW = 3,
+       SALUS_EV_LANE_GROW = 4, SALUS_EV_LANE_DEL = 5, SALUS_EV_LANE_MOVED = 6, SALUS_EV_COMPACT = 7 };
+
+/* kind ADMIT: a = job, b = lane | EVICT: a = job, b = bytes | RESTORE: a = job,
+ * b = new persistent offset | LANE_NEW / LANE_GROW: a = lane, b = size |
+ * LANE_DEL: a = lane | LANE_MOVED: a = number of lanes that slid | COMPACT:
+ * a = moves, b = bytes moved. */
+typedef struct { int32_t kind; int32_t pad; uint64_t a, b; } salus_event;
+
+/* Section 3.3: split [base, base+capacity) into a persistent region growing up
+ * from offset 0 and an ephemeral region (lanes) growing down from `capacity`.
+ * base: device pointer, 256-byte aligned, owned by the caller and alive until
+ * salus_pool_destroy; may be NULL for a metadata-only pool (every call that
+ * would touch device memory then fails with SALUS_EINVAL, except that layout
+ * calls simply skip the copies).  capacity must be a multiple of the granule. */
+int32_t salus_pool_create(void *base, uint64_t capacity, const salus_config *cfg,
+                          salus_pool_t **out);
+int32_t salus_pool_destroy(salus_pool_t *pool);
+
+/* Algorithm 1, JobArrive(P, E) followed by ProcessRequests: the request joins
+ * the pending queue and every queued request is offered to FindLane (new lane,
+ * else best matching existing lane, else grow the smallest lane that makes it
+ * fit), always under  sum P_i + sum L_j <= C.  The job's persistent block is
+ * placed first-fit at the lowest address below the ephemeral region; live
+ * blocks are compacted on the device first when no single hole is big enough
+ * or when the new lane needs the space they occupy.  Under
+ * SALUS_POLICY_PRIORITY a request that finds no lane evicts resident jobs of
+ * strictly lower priority to pinned host memory (Section 4.2), as few as
+ * needed.  priority: larger = more urgent.  pending: iterations to run
+ * (remaining time for SRTF); may be 0 and set later.
+ * Returns SALUS_OK (resident now), SALUS_QUEUED, SALUS_ENEVER, SALUS_EINVAL. */
+int32_t salus_lane_alloc(salus_pool_t *pool, uint64_t P, uint64_t E, int32_t priority,
+                         uint64_t pending, int32_t *job);
+
+/* Algorithm 1, JobFinish: frees the persistent block (and any host copy),
+ * drops the lane reference; an empty lane is deleted and younger lanes slide
+ * into its place without any copy (Section 3.3.1).  Then the queue is
+ * processed and automatically evicted jobs that fit again are restored. */
+int32_t salus_lane_free(salus_pool_t *pool, int32_t job);
+
+int32_t salus_job_query(salus_pool_t *pool, int32_t job, salus_job_info *out);
+int32_t salus_job_set_pending(salus_pool_t *pool, int32_t job, uint64_t n);
+
+/* Copy bytes between host memory and a resident job's persistent block
+ * (synchronous; for loading weights and reading them back). */
+int32_t salus_job_write(salus_pool_t *pool, int32_t job, uint64_t off, const void *host_src,
+                        uint64_t nbytes);
+int32_t salus_job_read(salus_pool_t *pool, int32_t job, uint64_t off, void *host_dst,
+                       uint64_t nbytes);
+
+/* Sections 3.3 and 4: one scheduling round.  Picks at most one resident job
+ * with pending > 0 per lane according to the policy, charges it one iteration
+ * (served + 1, pending - 1) and writes the (job, lane) pairs in lane creation
+ * order to out[0..*n).  cap must be >= the number of lanes. */
+int32_t salus_schedule_iteration(salus_pool_t *pool, salus_slot *out, uint32_t cap, uint32_t *n);
+
+/* Packed iteration (Section 3.3: lanes run in parallel): the forward passes of
+ * all n jobs run together, one grouped GEMM launch per layer depth on `stream`
+ * (hipStream_t, NULL = default), asynchronously.  Jobs must be resident and
+ * belong to pairwise different lanes (SALUS_EBUSY otherwise); every buffer
+ * must lie inside the job's lane / persistent block (SALUS_EINVAL).  K and N
+ * of every layer must be multiples of 8 (bf16) or 4 (f32). */
+int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
+                              void *stream);
+
+/* Efficient job switching made explicit for jobs that cannot stay
+ * (Sections 3.2 and 4.2): RESIDENT -> EVICTED copies the persistent block to
+ * pinned host memory and frees it.  pinned_or_null: caller-owned pinned,
+ * device-mapped buffer of at least P bytes that stays valid until the job is
+ * switched in or freed; NULL = the library allocates (and caches) one.
+ * Synchronous with respect to the pool's stream on return. */
+int32_t salus_switch_out(salus_pool_t *pool, int32_t job, void *pinned_or_null);
+/* EVICTED -> RESIDENT: first-fit placement (compacting if needed), then copy back. */
+int32_t salus_switch_in(salus_pool_t *pool, int32_t job);
+
+/* Slide all live persistent blocks to the low end in address order; new offset
+ * = exclusive prefix sum of the granule-rounded sizes.  Executes the moves on
+ * the device (overlap-safe) and writes the plan to plan_out[0..*n_moves)
+ * (at most cap entries are written; *n_moves is the full count). */
+int32_t salus_compact(salus_pool_t *pool, salus_move *plan_out, uint32_t cap, uint32_t *n_moves);
+
+int32_t salus_get_stats(salus_pool_t *pool, salus_stats *out);
+/* Copies and clears the event log (at most cap entries; *n = entries copied). */
+int32_t salus_poll_events(salus_pool_t *pool, salus_event *out, uint32_t cap, uint32_t *n);
+/* Lane ids in creation order with their current base and size. */
+int32_t salus_lanes(salus_pool_t *pool, int32_t *ids, uint64_t *offs, uint64_t *sizes,
+                    uint32_t cap, uint32_t *n);
+const char *salus_last_error(salus_pool_t *pool);
+
+/* Device self-checks used by the tests (each is synchronous).
+ * salus_scan_u64: exclusive prefix sum of n (<= 4096) host integers computed
+ * by the wavefront scan the kernels use; result to host out[0..n], out[n] =
+ * total.  scratch: device pointer to at least (2*n+2)*8 bytes.
+ * salus_fill_pattern / salus_check_pattern: write / verify the 64-bit pattern
+ * f(seed, index) over a device range (nbytes multiple of 8); check returns the
+ * number of mismatching words in *bad (scratch: 8 device bytes). */
+int32_t salus_scan_u64(const uint64_t *host_in, uint32_t n, uint64_t *host_out, void *scratch,
+                       void *stream);
+int32_t salus_fill_pattern(void *dev, uint64_t nbytes, uint64_t seed, void *stream);
+int32_t salus_check_pattern(const void *dev, uint64_t nbytes, uint64_t seed, void *scratch,
+                            uint64_t *bad, void *stream);
+/* Plain device copy with the library's copy kernel (memmove semantics when the
+ * ranges overlap with dst < src). */
+int32_t salus_copy(void *dst, const void *src, uint64_t nbytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,421 @@
+// C ABI of the library (declared in include/salus.h): argument checking, the
+// HIP implementation of the data-movement interface the host logic uses, and
+// the translation of job descriptors into grouped-GEMM problem lists.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "device.hpp"
+#include "pool_core.hpp"
+#include "salus.h"
+
+using namespace salus;
+
+namespace {
+
+struct HipOps : DeviceOps {
+    char *base = nullptr;
+    uint64_t capacity = 0;
+    hipStream_t stream = nullptr;
+    int engine = SALUS_COPY_KERNEL;
+    std::string *error = nullptr;
+    uint64_t copy_launches = 0;
+
+    bool present() const override { return base != nullptr; }
+
+    int fail(hipError_t e, const char *what)
+    {
+        if (error) *error = std::string(what) + ": " + hipGetErrorString(e);
+        return -1;
+    }
+
+    int host_copy(void *dst, const void *src, uint64_t n, hipMemcpyKind kind)
+    {
+        if (n == 0) return 0;
+        hipError_t e;
+        if (engine == SALUS_COPY_KERNEL) {
+            // the kernel reads / writes the pinned buffer through its device mapping
+            void *mapped = nullptr;
+            void *host = kind == hipMemcpyDeviceToHost ? dst : const_cast<void *>(src);
+            e = hipHostGetDevicePointer(&mapped, host, 0);
+            if (e != hipSuccess) return fail(e, "hipHostGetDevicePointer");
+            CopySeg seg = kind == hipMemcpyDeviceToHost ? CopySeg{src, mapped, n}
+                                                        : CopySeg{mapped, dst, n};
+            e = launch_copy(&seg, 1, stream);
+            copy_launches += 1;
+        } else {
+            e = hipMemcpyAsync(dst, src, n, kind, stream);
+        }
+        if (e != hipSuccess) return fail(e, "host link copy");
+        e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) return fail(e, "hipStreamSynchronize");
+        return 0;
+    }
+
+    int evict(void *host, uint64_t off, uint64_t n) override
+    {
+        return host_copy(host, base + off, n, hipMemcpyDeviceToHost);
+    }
+    int restore(uint64_t off, const void *host, uint64_t n) override
+    {
+        return host_copy(base + off, host, n, hipMemcpyHostToDevice);
+    }
+    int slide(const salus_move *m, uint32_t n, uint64_t free_off, uint64_t free_len) override
+    {
+        std::vector<uint64_t> s(n), d(n), l(n);
+        for (uint32_t i = 0; i < n; ++i) { s[i] = m[i].src; d[i] = m[i].dst; l[i] = m[i].len; }
+        hipError_t e = launch_slide(base, s.data(), d.data(), l.data(), n, free_off, free_len,
+                                    stream, &copy_launches);
+        if (e != hipSuccess) return fail(e, "compaction launch");
+        e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) return fail(e, "hipStreamSynchronize");
+        return 0;
+    }
+    void *pinned_alloc(uint64_t n) override
+    {
+        void *p = nullptr;
+        if (hipHostMalloc(&p, n, hipHostMallocMapped | hipHostMallocPortable) != hipSuccess) return nullptr;
+        return p;
+    }
+    void pinned_free(void *p) override { (void)hipHostFree(p); }
+};
+
+}  // namespace
+
+struct salus_pool {
+    HipOps ops;
+    std::unique_ptr<PoolCore> core;
+    std::string error;
+    uint64_t granule = 256;
+    uint64_t gemm_launches = 0;
+};
+
+#define CHECK_POOL(p) \
+    if (!(p)) return SALUS_EINVAL
+
+static int32_t set_error(salus_pool *p, int32_t code, const std::string &msg)
+{
+    p->error = msg;
+    return code;
+}
+
+static int32_t done(salus_pool *p, int32_t rc)
+{
+    if (rc < 0 && !p->core->error.empty()) p->error = p->core->error;
+    return rc;
+}
+
+extern "C" {
+
+int32_t salus_pool_create(void *base, uint64_t capacity, const salus_config *cfg, salus_pool_t **out)
+{
+    if (!out) return SALUS_EINVAL;
+    *out = nullptr;
+    salus_config c{};
+    if (cfg) c = *cfg;
+    if (c.granule == 0) c.granule = 256;
+    if (c.granule < 16 || (c.granule & (c.granule - 1))) return SALUS_EINVAL;
+    if (capacity == 0 || capacity % c.granule) return SALUS_EINVAL;
+    if ((uintptr_t)base % 256) return SALUS_EINVAL;
+    if (c.policy < SALUS_POLICY_FIFO || c.policy > SALUS_POLICY_PACK) return SALUS_EINVAL;
+    if (c.copy_engine != SALUS_COPY_KERNEL && c.copy_engine != SALUS_COPY_DMA) return SALUS_EINVAL;
+    salus_pool *p = new (std::nothrow) salus_pool;
+    if (!p) return SALUS_ENOMEM;
+    p->ops.base = (char *)base;
+    p->ops.capacity = capacity;
+    p->ops.stream = (hipStream_t)c.stream;
+    p->ops.engine = c.copy_engine;
+    p->ops.error = &p->error;
+    p->granule = c.granule;
+    p->core.reset(new PoolCore(capacity, c.granule, c.max_lanes, c.policy, &p->ops));
+    *out = p;
+    return SALUS_OK;
+}
+
+int32_t salus_pool_destroy(salus_pool_t *pool)
+{
+    CHECK_POOL(pool);
+    delete pool;
+    return SALUS_OK;
+}
+
+int32_t salus_lane_alloc(salus_pool_t *pool, uint64_t P, uint64_t E, int32_t priority,
+                         uint64_t pending, int32_t *job)
+{
+    CHECK_POOL(pool);
+    return done(pool, pool->core->arrive(P, E, priority, pending, job));
+}
+
+int32_t salus_lane_free(salus_pool_t *pool, int32_t job)
+{
+    CHECK_POOL(pool);
+    return done(pool, pool->core->finish(job));
+}
+
+int32_t salus_job_query(salus_pool_t *pool, int32_t job, salus_job_info *out)
+{
+    CHECK_POOL(pool);
+    int32_t rc = pool->core->query(job, out);
+    if (rc) return set_error(pool, rc, "no such job");
+    return rc;
+}
+
+int32_t salus_job_set_pending(salus_pool_t *pool, int32_t job, uint64_t n)
+{
+    CHECK_POOL(pool);
+    return done(pool, pool->core->set_pending(job, n));
+}
+
+static int32_t job_io(salus_pool *pool, int32_t job, uint64_t off, void *host, uint64_t n, bool write)
+{
+    const Job *j = pool->core->job(job);
+    if (!j || !host) return set_error(pool, SALUS_EINVAL, "bad job or buffer");
+    if (j->state != SALUS_JOB_RESIDENT) return set_error(pool, SALUS_ENOTRESIDENT, "job is not resident");
+    if (off > j->P || n > j->P - off) return set_error(pool, SALUS_EINVAL, "range outside the persistent block");
+    if (!pool->ops.present()) return set_error(pool, SALUS_EINVAL, "pool has no device memory");
+    char *dev = pool->ops.base + j->off + off;
+    hipError_t e = write ? hipMemcpyAsync(dev, host, n, hipMemcpyHostToDevice, pool->ops.stream)
+                         : hipMemcpyAsync(host, dev, n, hipMemcpyDeviceToHost, pool->ops.stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(pool->ops.stream);
+    if (e != hipSuccess) return set_error(pool, SALUS_EHIP, hipGetErrorString(e));
+    return SALUS_OK;
+}
+
+int32_t salus_job_write(salus_pool_t *pool, int32_t job, uint64_t off, const void *host_src,
+                        uint64_t nbytes)
+{
+    CHECK_POOL(pool);
+    return job_io(pool, job, off, const_cast<void *>(host_src), nbytes, true);
+}
+
+int32_t salus_job_read(salus_pool_t *pool, int32_t job, uint64_t off, void *host_dst, uint64_t nbytes)
+{
+    CHECK_POOL(pool);
+    return job_io(pool, job, off, host_dst, nbytes, false);
+}
+
+int32_t salus_schedule_iteration(salus_pool_t *pool, salus_slot *out, uint32_t cap, uint32_t *n)
+{
+    CHECK_POOL(pool);
+    return done(pool, pool->core->schedule(out, cap, n));
+}
+
+static bool overlap(uint64_t a, uint64_t an, uint64_t b, uint64_t bn)
+{
+    return an && bn && a < b + bn && b < a + an;
+}
+
+int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
+                              void *stream)
+{
+    CHECK_POOL(pool);
+    if (n == 0) return SALUS_OK;
+    if (!descs) return set_error(pool, SALUS_EINVAL, "null descriptor array");
+    if (!pool->ops.present()) return set_error(pool, SALUS_EINVAL, "pool has no device memory");
+    char *base = pool->ops.base;
+    uint32_t depth = 0;
+    std::vector<int32_t> lanes_used;
+    struct Resolved { char *w, *x, *y, *h; uint64_t hstride; uint32_t esz; };
+    std::vector<Resolved> res(n);
+    for (uint32_t i = 0; i < n; ++i) {
+        const salus_gemm_desc &d = descs[i];
+        const Job *j = pool->core->job(d.job);
+        if (!j) return set_error(pool, SALUS_EINVAL, "descriptor names an unknown job");
+        if (j->state != SALUS_JOB_RESIDENT)
+            return set_error(pool, SALUS_ENOTRESIDENT, "job " + std::to_string(d.job) + " is not resident");
+        if (std::find(lanes_used.begin(), lanes_used.end(), j->lane) != lanes_used.end())
+            return set_error(pool, SALUS_EBUSY, "two jobs of lane " + std::to_string(j->lane) +
+                                                    " in one packed iteration");
+        lanes_used.push_back(j->lane);
+        if (d.dtype != SALUS_F32 && d.dtype != SALUS_BF16) return set_error(pool, SALUS_EINVAL, "bad dtype");
+        if (d.n_layers == 0 || !d.layers || d.M == 0) return set_error(pool, SALUS_EINVAL, "empty job descriptor");
+        const uint32_t esz = d.dtype == SALUS_BF16 ? 2 : 4;
+        const uint32_t mult = 16 / esz;
+        uint64_t lane_size = 0;
+        const uint64_t lane_off = pool->core->lane_base(j->lane, &lane_size);
+        uint32_t max_n = 0;
+        for (uint32_t l = 0; l < d.n_layers; ++l) {
+            const salus_layer &L = d.layers[l];
+            if (L.K == 0 || L.N == 0 || L.K % mult || L.N % mult)
+                return set_error(pool, SALUS_EINVAL, "K and N must be positive multiples of 16 bytes");
+            if (l && L.K != d.layers[l - 1].N) return set_error(pool, SALUS_EINVAL, "layer widths do not chain");
+            if (L.act < SALUS_ACT_NONE || L.act > SALUS_ACT_GELU) return set_error(pool, SALUS_EINVAL, "bad activation");
+            const uint64_t wbytes = (uint64_t)L.K * L.N * esz;
+            if (L.w_off % 16 || L.w_off > j->P || wbytes > j->P - L.w_off)
+                return set_error(pool, SALUS_EINVAL, "weights outside the persistent block");
+            if (l + 1 < d.n_layers) max_n = std::max(max_n, L.N);
+        }
+        const uint64_t xbytes = (uint64_t)d.M * d.layers[0].K * esz;
+        const uint64_t ybytes = (uint64_t)d.M * d.layers[d.n_layers - 1].N * 4;
+        const uint64_t hstride = ((uint64_t)d.M * max_n * esz + 255) & ~(uint64_t)255;
+        const uint64_t hbytes = d.n_layers > 1 ? 2 * hstride : 0;
+        auto inside = [&](uint64_t off, uint64_t nb) { return off % 16 == 0 && off <= lane_size && nb <= lane_size - off; };
+        if (!inside(d.x_off, xbytes) || !inside(d.y_off, ybytes) || !inside(d.h_off, hbytes))
+            return set_error(pool, SALUS_EINVAL, "buffer outside the job's lane");
+        if (overlap(d.x_off, xbytes, d.y_off, ybytes) || overlap(d.x_off, xbytes, d.h_off, hbytes) ||
+            overlap(d.y_off, ybytes, d.h_off, hbytes))
+            return set_error(pool, SALUS_EINVAL, "x, y and h ranges overlap");
+        res[i] = {base + j->off, base + lane_off + d.x_off, base + lane_off + d.y_off,
+                  base + lane_off + d.h_off, hstride, esz};
+        depth = std::max(depth, d.n_layers);
+    }
+    // one grouped launch per layer depth over all jobs that have that layer
+    std::vector<Problem> probs;
+    for (int dt = SALUS_F32; dt <= SALUS_BF16; ++dt) {
+        for (uint32_t l = 0; l < depth; ++l) {
+            probs.clear();
+            for (uint32_t i = 0; i < n; ++i) {
+                const salus_gemm_desc &d = descs[i];
+                if (d.dtype != dt || l >= d.n_layers) continue;
+                const salus_layer &L = d.layers[l];
+                const bool last = l + 1 == d.n_layers;
+                Problem pr;
+                pr.W = res[i].w + L.w_off;
+                pr.X = l == 0 ? res[i].x : res[i].h + ((l - 1) & 1) * res[i].hstride;
+                pr.Y = last ? res[i].y : res[i].h + (l & 1) * res[i].hstride;
+                pr.M = d.M;
+                pr.K = L.K;
+                pr.N = L.N;
+                pr.flags = (uint32_t)L.act | ((!last && dt == SALUS_BF16) ? kOutBf16 : 0u);
+                probs.push_back(pr);
+            }
+            if (probs.empty()) continue;
+            hipError_t e = dt == SALUS_BF16
+                               ? launch_grouped_bf16(probs.data(), (uint32_t)probs.size(), (hipStream_t)stream, &pool->gemm_launches)
+                               : launch_grouped_f32(probs.data(), (uint32_t)probs.size(), (hipStream_t)stream, &pool->gemm_launches);
+            if (e != hipSuccess) return set_error(pool, SALUS_EHIP, hipGetErrorString(e));
+        }
+    }
+    return SALUS_OK;
+}
+
+int32_t salus_switch_out(salus_pool_t *pool, int32_t job, void *pinned_or_null)
+{
+    CHECK_POOL(pool);
+    return done(pool, pool->core->switch_out(job, pinned_or_null));
+}
+
+int32_t salus_switch_in(salus_pool_t *pool, int32_t job)
+{
+    CHECK_POOL(pool);
+    return done(pool, pool->core->switch_in(job));
+}
+
+int32_t salus_compact(salus_pool_t *pool, salus_move *plan_out, uint32_t cap, uint32_t *n_moves)
+{
+    CHECK_POOL(pool);
+    std::vector<salus_move> plan;
+    int32_t rc = pool->core->compact(&plan);
+    if (n_moves) *n_moves = (uint32_t)plan.size();
+    if (plan_out)
+        for (uint32_t i = 0; i < cap && i < plan.size(); ++i) plan_out[i] = plan[i];
+    return done(pool, rc);
+}
+
+int32_t salus_get_stats(salus_pool_t *pool, salus_stats *out)
+{
+    CHECK_POOL(pool);
+    if (!out) return SALUS_EINVAL;
+    *out = pool->core->stats;
+    out->gemm_launches = pool->gemm_launches;
+    out->queued = pool->core->queued();
+    return SALUS_OK;
+}
+
+int32_t salus_poll_events(salus_pool_t *pool, salus_event *out, uint32_t cap, uint32_t *n)
+{
+    CHECK_POOL(pool);
+    if (!n) return SALUS_EINVAL;
+    std::vector<salus_event> &ev = pool->core->events;
+    uint32_t k = (uint32_t)std::min<size_t>(cap, ev.size());
+    if (!out) k = 0;
+    for (uint32_t i = 0; i < k; ++i) out[i] = ev[i];
+    ev.erase(ev.begin(), ev.begin() + k);
+    *n = k;
+    return SALUS_OK;
+}
+
+int32_t salus_lanes(salus_pool_t *pool, int32_t *ids, uint64_t *offs, uint64_t *sizes, uint32_t cap,
+                    uint32_t *n)
+{
+    CHECK_POOL(pool);
+    if (!n) return SALUS_EINVAL;
+    const std::vector<Lane> &lanes = pool->core->lanes();
+    uint64_t top = pool->core->capacity();
+    uint32_t k = 0;
+    for (const Lane &l : lanes) {
+        top -= l.size;
+        if (k < cap) {
+            if (ids) ids[k] = l.id;
+            if (offs) offs[k] = top;
+            if (sizes) sizes[k] = l.size;
+            ++k;
+        }
+    }
+    *n = (uint32_t)lanes.size();
+    return SALUS_OK;
+}
+
+const char *salus_last_error(salus_pool_t *pool) { return pool ? pool->error.c_str() : "null pool"; }
+
+// ---- device self-checks ------------------------------------------------------
+int32_t salus_scan_u64(const uint64_t *host_in, uint32_t n, uint64_t *host_out, void *scratch,
+                       void *stream)
+{
+    if (!host_in || !host_out || !scratch || n > 4096) return SALUS_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    uint64_t *in = (uint64_t *)scratch, *out = in + n;
+    hipError_t e = hipMemcpyAsync(in, host_in, (size_t)n * 8, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = launch_scan_u64(in, n, out, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(host_out, out, ((size_t)n + 1) * 8, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    return e == hipSuccess ? SALUS_OK : SALUS_EHIP;
+}
+
+int32_t salus_fill_pattern(void *dev, uint64_t nbytes, uint64_t seed, void *stream)
+{
+    if (!dev || nbytes % 8 || (uintptr_t)dev % 8) return SALUS_EINVAL;
+    hipError_t e = launch_fill_pattern(dev, nbytes, seed, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    return e == hipSuccess ? SALUS_OK : SALUS_EHIP;
+}
+
+int32_t salus_check_pattern(const void *dev, uint64_t nbytes, uint64_t seed, void *scratch,
+                            uint64_t *bad, void *stream)
+{
+    if (!dev || !scratch || !bad || nbytes % 8 || (uintptr_t)dev % 8) return SALUS_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    unsigned long long zero = 0, got = 0;
+    hipError_t e = hipMemcpyAsync(scratch, &zero, 8, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = launch_check_pattern(dev, nbytes, seed, (unsigned long long *)scratch, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(&got, scratch, 8, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    *bad = got;
+    return e == hipSuccess ? SALUS_OK : SALUS_EHIP;
+}
+
+int32_t salus_copy(void *dst, const void *src, uint64_t nbytes, void *stream)
+{
+    if (!dst || !src || nbytes % 16 || (uintptr_t)dst % 16 || (uintptr_t)src % 16) return SALUS_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    const char *sp = (const char *)src;
+    char *dp = (char *)dst;
+    if (dp + nbytes <= sp || sp + nbytes <= dp) {
+        CopySeg seg{src, dst, nbytes};
+        e = launch_copy(&seg, 1, s);
+    } else if (dp < sp) {
+        uint64_t so = (uint64_t)(sp - dp), zo = 0, len = nbytes;   // offsets relative to dst
+        e = launch_slide(dp, &so, &zo, &len, 1, 0, 0, s, nullptr);
+    } else {
+        return SALUS_EINVAL;    // moving upward with overlap is never needed by the pool
+    }
+    return e == hipSuccess ? SALUS_OK : SALUS_EHIP;
+}
+
+}  // extern "C"

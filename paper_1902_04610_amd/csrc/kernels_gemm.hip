@@ -1,0 +1,357 @@
+// Grouped dense-layer kernels for gfx950 (MI355X): one launch runs one layer of
+// every job scheduled in the round.  This is how "parallelism across lanes"
+// (Salus paper, Section 3.3) is executed here: instead of one GPU stream per
+// lane, the tiles of all lanes' jobs share one grid, and each workgroup finds
+// its job with a wavefront scan over the per-job tile counts.
+//
+// Shape of the work: per job Y[M x N] = act(X[M x K] . W[K x N]) with M small
+// (1..64 rows) and W read straight out of the job's persistent block.  Every
+// weight is used once per launch, so the kernel is a weight-streaming kernel:
+// W goes HBM -> registers with 16-byte loads (no LDS staging: nothing would be
+// reused), each wavefront keeps two k-steps of loads in flight, the 8x8 bf16
+// sub-blocks are transposed in registers into MFMA operand order, and the four
+// wavefronts of a workgroup split K and combine their partial tiles through LDS.
+#include <algorithm>
+
+#include "device.hpp"
+#include "wave.hpp"
+
+namespace salus {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct GroupArgs {
+    uint32_t n;
+    uint32_t pad;
+    Problem p[kMaxProblems];
+};
+
+constexpr int kGemmThreads = 256;
+constexpr int kWaves = 4;
+
+__device__ inline float activate(float z, uint32_t act)
+{
+    if (act == 1) return fmaxf(z, 0.0f);
+    if (act == 2) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
+    return z;
+}
+
+// float -> bf16 bits, round to nearest, ties to even.
+__device__ inline uint32_t bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); map
+// the hardware index to a logical one so that every XCD works on a contiguous
+// range of tiles - the tiles of one job share its activations in one L2.
+__device__ inline uint32_t xcd_remap(uint32_t b, uint32_t total)
+{
+    const uint32_t x = b & 7u, slot = b >> 3;
+    const uint32_t q = total >> 3, r = total & 7u;
+    return x * q + (x < r ? x : r) + slot;
+}
+
+struct Tile {
+    int problem;
+    uint32_t m0, n0;
+};
+
+// Which (job, row tile, column tile) this workgroup owns: lane i of every
+// wavefront holds job i's tile count; an exclusive scan gives each job's first
+// tile; a ballot finds the job whose range contains this workgroup's index.
+template <int TM, int TN>
+__device__ inline Tile find_tile(const GroupArgs &a)
+{
+    const int lane = threadIdx.x & 63;
+    const bool valid = lane < (int)a.n;
+    uint32_t row_tiles = 0, count = 0;
+    if (valid) {
+        row_tiles = (a.p[lane].M + TM - 1) / TM;
+        count = row_tiles * ((a.p[lane].N + TN - 1) / TN);
+    }
+    const uint32_t first = wave_excl_scan_u32(count, nullptr);
+    const uint32_t id = xcd_remap(blockIdx.x, gridDim.x);
+    const int g = wave_find_range(first, id, valid);
+    const uint32_t t = id - __shfl(first, g, 64);
+    const uint32_t rt = __shfl(row_tiles, g, 64);
+    Tile tile;
+    tile.problem = __builtin_amdgcn_readfirstlane(g);
+    tile.m0 = (t % rt) * TM;      // row tiles of one column tile are neighbours: they share W
+    tile.n0 = (t / rt) * TN;
+    return tile;
+}
+
+// Combine the four wavefronts' partial tiles.  Accumulator register r (0..3)
+// of every 16x16 block holds row 4*(lane/16)+r, so wavefront w ends up owning
+// rows with r == w: each wavefront sends the other three quarters through LDS
+// and adds what it receives in a fixed order.
+template <int NACC>
+__device__ inline void reduce_scatter(f32x4 (&acc)[NACC], float (&own)[NACC], float *lds)
+{
+    constexpr int G = NACC < 16 ? NACC : 16;    // accumulators per pass (bounds the LDS footprint)
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // lds[dst wave][source slot][accumulator in pass][lane]
+#pragma unroll
+    for (int base = 0; base < NACC; base += G) {
+        if (base) __syncthreads();              // the previous pass has been read
+#pragma unroll
+        for (int d = 0; d < kWaves; ++d) {
+            if (d == wave) continue;
+            const int slot = (wave - d - 1) & 3;
+            float *to = lds + ((d * 3 + slot) * G) * 64 + lane;
+#pragma unroll
+            for (int i = 0; i < G; ++i) to[i * 64] = acc[base + i][d];
+        }
+        __syncthreads();
+        const float *from = lds + (wave * 3 * G) * 64 + lane;
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            const f32x4 mine = acc[base + i];
+            float v = wave == 0 ? mine[0] : wave == 1 ? mine[1] : wave == 2 ? mine[2] : mine[3];
+            v += from[(0 * G + i) * 64];
+            v += from[(1 * G + i) * 64];
+            v += from[(2 * G + i) * 64];
+            own[base + i] = v;
+        }
+    }
+}
+
+template <int NACC>
+constexpr int reduce_lds_floats() { return kWaves * 3 * (NACC < 16 ? NACC : 16) * 64; }
+
+// ---------------------------------------------------------------------------
+// bf16 weights and activations, float accumulation, v_mfma_f32_16x16x32_bf16.
+// Tile: TM = 16*MT rows x 128 columns.  Lane (c = lane%16, g = lane/16) of a
+// wavefront loads, per k-step of 32 rows, the 8x8 block W[k0+8g .. +7][n0+8c ..
+// +7] (eight 16-byte loads, 256 contiguous bytes per row across the 16 lanes)
+// and transposes it in registers; column i of the block is the B operand of
+// MFMA i, whose 16 output columns are n0 + 8c + i.  The A operand is
+// X[m0 + c][k0+8g .. +7].  Both operands use the same 8 k-values per lane
+// group, which is all the MFMA contraction needs.
+// ---------------------------------------------------------------------------
+template <int MT>
+__global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
+{
+    constexpr int TM = 16 * MT, TN = 128, NACC = MT * 8;
+    __shared__ float lds[reduce_lds_floats<NACC>()];
+    const Tile tile = find_tile<TM, TN>(a);
+    const Problem &p = a.p[tile.problem];
+    const uint32_t M = p.M, K = p.K, N = p.N;
+    const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
+    const int wave = threadIdx.x >> 6;
+    const uint32_t ncol = tile.n0 + 8 * c;
+    const bool col_ok = ncol < N;
+    const uint16_t *W = (const uint16_t *)p.W;
+    const uint16_t *X = (const uint16_t *)p.X;
+
+    f32x4 acc[NACC];
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int nsteps = (int)((K + 31) / 32);
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+
+    auto load = [&](int s, u32x4 (&w)[8], u32x4 (&x)[MT]) {
+        const uint32_t kb = 32u * (uint32_t)s + 8u * (uint32_t)g;
+        const bool k_ok = s < nsteps && kb < K;
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+            w[r] = (k_ok && col_ok)
+                       ? __builtin_nontemporal_load((const u32x4 *)(W + (size_t)(kb + r) * N + ncol))
+                       : zero;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const uint32_t row = tile.m0 + 16 * t + c;
+            x[t] = (k_ok && row < M) ? *(const u32x4 *)(X + (size_t)row * K + kb) : zero;
+        }
+    };
+    auto compute = [&](const u32x4 (&w)[8], const u32x4 (&x)[MT]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            // column i of the 8x8 block: dword j = (row 2j, row 2j+1)
+            u32x4 b;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                b[j] = __builtin_amdgcn_perm(w[2 * j + 1][i >> 1], w[2 * j][i >> 1],
+                                             (i & 1) ? 0x07060302u : 0x05040100u);
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+                acc[t * 8 + i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    __builtin_bit_cast(bf16x8, x[t]), __builtin_bit_cast(bf16x8, b), acc[t * 8 + i],
+                    0, 0, 0);
+        }
+    };
+
+    // the four wavefronts take k-steps wave, wave+4, ...; two steps stay in flight
+    u32x4 w0[8], w1[8], x0[MT], x1[MT];
+    int s = wave;
+    load(s, w0, x0);
+    load(s + kWaves, w1, x1);
+    for (; s < nsteps; s += 2 * kWaves) {
+        compute(w0, x0);
+        load(s + 2 * kWaves, w0, x0);
+        compute(w1, x1);
+        load(s + 3 * kWaves, w1, x1);
+    }
+
+    float own[NACC];
+    reduce_scatter<NACC>(acc, own, lds);
+
+    const uint32_t act = p.flags & 0xffu;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const uint32_t row = tile.m0 + 16 * t + 4 * g + wave;
+        if (row >= M || !col_ok) continue;
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = activate(own[t * 8 + i], act);
+        if (p.flags & kOutBf16) {
+            u32x4 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j] = bf16_bits(v[2 * j]) | (bf16_bits(v[2 * j + 1]) << 16);
+            *(u32x4 *)((uint16_t *)p.Y + (size_t)row * N + ncol) = o;
+        } else {
+            float *y = (float *)p.Y + (size_t)row * N + ncol;
+            *(f32x4 *)y = f32x4{v[0], v[1], v[2], v[3]};
+            *(f32x4 *)(y + 4) = f32x4{v[4], v[5], v[6], v[7]};
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// float weights and activations, v_mfma_f32_16x16x4_f32 (true fp32 products).
+// Tile: 16*MT rows x 64 columns; a k-step covers 16 rows of W.  Lane (c, g)
+// loads W[k0+4g+q][n0+4c .. +3] for q = 0..3 and X[m0+c][k0+4g .. +3]; MFMA
+// (q, i) multiplies component q of X with component i of W row q, so lane
+// group g contributes k = k0+4g+q in step q and output column n0+4c+i.
+// ---------------------------------------------------------------------------
+template <int MT>
+__global__ __launch_bounds__(kGemmThreads) void grouped_dense_f32(GroupArgs a)
+{
+    constexpr int TM = 16 * MT, TN = 64, NACC = MT * 4;
+    __shared__ float lds[reduce_lds_floats<NACC>()];
+    const Tile tile = find_tile<TM, TN>(a);
+    const Problem &p = a.p[tile.problem];
+    const uint32_t M = p.M, K = p.K, N = p.N;
+    const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
+    const int wave = threadIdx.x >> 6;
+    const uint32_t ncol = tile.n0 + 4 * c;
+    const bool col_ok = ncol < N;
+    const float *W = (const float *)p.W;
+    const float *X = (const float *)p.X;
+
+    f32x4 acc[NACC];
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int nsteps = (int)((K + 15) / 16);
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+
+    auto load = [&](int s, f32x4 (&w)[4], f32x4 (&x)[MT]) {
+        const uint32_t kb = 16u * (uint32_t)s + 4u * (uint32_t)g;
+        const bool k_ok = s < nsteps && kb < K;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            w[q] = (k_ok && col_ok) ? *(const f32x4 *)(W + (size_t)(kb + q) * N + ncol) : zero;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const uint32_t row = tile.m0 + 16 * t + c;
+            x[t] = (k_ok && row < M) ? *(const f32x4 *)(X + (size_t)row * K + kb) : zero;
+        }
+    };
+    auto compute = [&](const f32x4 (&w)[4], const f32x4 (&x)[MT]) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+                    acc[t * 4 + i] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[t][q], w[q][i],
+                                                                          acc[t * 4 + i], 0, 0, 0);
+    };
+
+    f32x4 w0[4], w1[4], x0[MT], x1[MT];
+    int s = wave;
+    load(s, w0, x0);
+    load(s + kWaves, w1, x1);
+    for (; s < nsteps; s += 2 * kWaves) {
+        compute(w0, x0);
+        load(s + 2 * kWaves, w0, x0);
+        compute(w1, x1);
+        load(s + 3 * kWaves, w1, x1);
+    }
+
+    float own[NACC];
+    reduce_scatter<NACC>(acc, own, lds);
+
+    const uint32_t act = p.flags & 0xffu;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const uint32_t row = tile.m0 + 16 * t + 4 * g + wave;
+        if (row >= M || !col_ok) continue;
+        f32x4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = activate(own[t * 4 + i], act);
+        *(f32x4 *)((float *)p.Y + (size_t)row * N + ncol) = o;
+    }
+}
+
+// ---------------------------------------------------------------------------
+template <typename Launch>
+static hipError_t launch_groups(const Problem *p, uint32_t n, uint32_t tn, uint32_t m_small,
+                                uint32_t m_mid, Launch launch, uint64_t *launches)
+{
+    for (uint32_t at = 0; at < n; at += kMaxProblems) {
+        GroupArgs a{};
+        a.n = std::min(kMaxProblems, n - at);
+        uint32_t max_m = 0;
+        for (uint32_t i = 0; i < a.n; ++i) {
+            a.p[i] = p[at + i];
+            max_m = std::max(max_m, a.p[i].M);
+        }
+        const int mt = max_m <= m_small ? 1 : max_m <= m_mid ? 2 : 4;
+        const uint32_t tm = 16u * mt;
+        uint64_t tiles = 0;
+        for (uint32_t i = 0; i < a.n; ++i)
+            tiles += (uint64_t)((a.p[i].M + tm - 1) / tm) * ((a.p[i].N + tn - 1) / tn);
+        if (tiles == 0) continue;
+        if (tiles > 0x7fffffffull) return hipErrorInvalidValue;
+        launch(mt, a, (uint32_t)tiles);
+        if (launches) *launches += 1;
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches)
+{
+    auto launch = [&](int mt, const GroupArgs &a, uint32_t tiles) {
+        if (mt == 1)
+            hipLaunchKernelGGL(grouped_dense_bf16<1>, dim3(tiles), dim3(kGemmThreads), 0, stream, a);
+        else if (mt == 2)
+            hipLaunchKernelGGL(grouped_dense_bf16<2>, dim3(tiles), dim3(kGemmThreads), 0, stream, a);
+        else
+            hipLaunchKernelGGL(grouped_dense_bf16<4>, dim3(tiles), dim3(kGemmThreads), 0, stream, a);
+    };
+    return launch_groups(p, n, 128, 16, 32, launch, launches);
+}
+
+hipError_t launch_grouped_f32(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches)
+{
+    auto launch = [&](int mt, const GroupArgs &a, uint32_t tiles) {
+        if (mt == 1)
+            hipLaunchKernelGGL(grouped_dense_f32<1>, dim3(tiles), dim3(kGemmThreads), 0, stream, a);
+        else if (mt == 2)
+            hipLaunchKernelGGL(grouped_dense_f32<2>, dim3(tiles), dim3(kGemmThreads), 0, stream, a);
+        else
+            hipLaunchKernelGGL(grouped_dense_f32<4>, dim3(tiles), dim3(kGemmThreads), 0, stream, a);
+    };
+    return launch_groups(p, n, 64, 16, 32, launch, launches);
+}
+
+}  // namespace salus

@@ -1,0 +1,409 @@
+// Host logic of the pool.  See pool_core.hpp for the map to the paper.
+#include "pool_core.hpp"
+
+#include <algorithm>
+
+namespace salus {
+
+static inline uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+PoolCore::PoolCore(uint64_t capacity, uint64_t granule, uint32_t max_lanes, int32_t policy,
+                   DeviceOps *dev)
+    : C_(capacity), A_(granule), max_lanes_(max_lanes), policy_(policy), dev_(dev) {}
+
+PoolCore::~PoolCore()
+{
+    for (Job &j : jobs_)
+        if (j.host && j.host_owned) dev_->pinned_free(j.host);
+}
+
+// Section 3.3: lanes are stacked downward from the top of the pool in creation
+// order, so a lane's base is a running sum over the lanes created before it and
+// a deleted lane's space is taken over by its younger neighbours without any
+// copy (Section 3.3.1).
+uint64_t PoolCore::lane_base(int32_t lane_id, uint64_t *size) const
+{
+    uint64_t top = C_;
+    for (const Lane &l : lanes_) {
+        top -= l.size;
+        if (l.id == lane_id) {
+            if (size) *size = l.size;
+            return top;
+        }
+    }
+    if (size) *size = 0;
+    return UINT64_MAX;
+}
+
+// FindLane of Algorithm 1 under the safety condition of Section 3.3.2.
+// residentP = persistent bytes of the jobs that would stay resident.
+PoolCore::Choice PoolCore::find_lane(uint64_t P, uint64_t E, uint64_t residentP) const
+{
+    const uint64_t S = residentP + P;
+    Choice c;
+    // 1. open a new lane
+    if ((max_lanes_ == 0 || lanes_.size() < max_lanes_) && S + sumL_ + E <= C_) {
+        c.kind = NEW;
+        return c;
+    }
+    // 2. share an existing lane that is large enough: least slack, then fewest
+    //    jobs, then oldest
+    if (S + sumL_ <= C_) {
+        bool found = false;
+        for (size_t i = 0; i < lanes_.size(); ++i) {
+            const Lane &l = lanes_[i];
+            if (l.size < E) continue;
+            if (!found) { found = true; c.index = i; continue; }
+            const Lane &b = lanes_[c.index];
+            if (l.size - E < b.size - E || (l.size == b.size && l.ref < b.ref)) c.index = i;
+        }
+        if (found) { c.kind = USE; return c; }
+    }
+    // 3. grow a lane that is too small, smallest first (oldest among equals)
+    std::vector<size_t> small;
+    for (size_t i = 0; i < lanes_.size(); ++i)
+        if (lanes_[i].size < E) small.push_back(i);
+    std::stable_sort(small.begin(), small.end(),
+                     [&](size_t a, size_t b) { return lanes_[a].size < lanes_[b].size; });
+    for (size_t i : small)
+        if (S + sumL_ - lanes_[i].size + E <= C_) {
+            c.kind = GROW;
+            c.index = i;
+            return c;
+        }
+    return c;
+}
+
+bool PoolCore::first_fit(uint64_t P, uint64_t fl, uint64_t *off) const
+{
+    uint64_t cur = 0;
+    for (const auto &kv : blocks_) {
+        if (kv.first >= cur + P && cur + P <= fl) { *off = cur; return true; }
+        cur = kv.first + jobs_[kv.second].P;
+    }
+    if (fl >= cur && fl - cur >= P) { *off = cur; return true; }
+    return false;
+}
+
+int PoolCore::do_compact(std::vector<salus_move> *plan_out)
+{
+    // New offset of each live block = exclusive prefix sum of the sizes below it.
+    std::vector<salus_move> plan;
+    std::map<uint64_t, int32_t> packed;
+    uint64_t next = 0, bytes = 0;
+    for (const auto &kv : blocks_) {
+        Job &j = jobs_[kv.second];
+        if (kv.first != next) {
+            plan.push_back({kv.first, next, j.P});
+            bytes += j.P;
+        }
+        packed.emplace_hint(packed.end(), next, kv.second);
+        next += j.P;
+    }
+    int rc = 0;
+    if (!plan.empty() && dev_->present()) {
+        const auto &top = *blocks_.rbegin();
+        const uint64_t high = round_up(top.first + jobs_[top.second].P, 256);
+        rc = dev_->slide(plan.data(), (uint32_t)plan.size(), high, high < C_ ? C_ - high : 0);
+    }
+    if (rc) { error = "device compaction failed"; return SALUS_EHIP; }
+    for (const auto &kv : packed) jobs_[kv.second].off = kv.first;
+    blocks_.swap(packed);
+    stats.compactions += 1;
+    stats.moves += plan.size();
+    stats.bytes_d2d += bytes;
+    log(SALUS_EV_COMPACT, plan.size(), bytes);
+    if (plan_out) plan_out->swap(plan);
+    return SALUS_OK;
+}
+
+int32_t PoolCore::compact(std::vector<salus_move> *plan) { return do_compact(plan); }
+
+int PoolCore::place(Job &j, uint64_t fl)
+{
+    uint64_t high = blocks_.empty() ? 0 : blocks_.rbegin()->first + jobs_[blocks_.rbegin()->second].P;
+    if (high > fl)
+        if (int rc = do_compact(nullptr)) return rc;
+    uint64_t off;
+    if (!first_fit(j.P, fl, &off)) {
+        if (int rc = do_compact(nullptr)) return rc;
+        if (!first_fit(j.P, fl, &off)) { error = "internal: safety condition violated"; return SALUS_ENOMEM; }
+    }
+    j.off = off;
+    blocks_[off] = j.id;
+    return SALUS_OK;
+}
+
+int PoolCore::admit(Job &j, Choice c)
+{
+    uint64_t new_floor = floor();
+    if (c.kind == NEW) new_floor -= j.E;
+    else if (c.kind == GROW) new_floor -= j.E - lanes_[c.index].size;
+    // persistent blocks in the way of the lane move down before the lane exists
+    uint64_t high = blocks_.empty() ? 0 : blocks_.rbegin()->first + jobs_[blocks_.rbegin()->second].P;
+    if (high > new_floor)
+        if (int rc = do_compact(nullptr)) return rc;
+    if (c.kind == NEW) {
+        lanes_.push_back({next_lane_++, j.E, 0});
+        c.index = lanes_.size() - 1;
+        sumL_ += j.E;
+        stats.lanes_opened += 1;
+        log(SALUS_EV_LANE_NEW, lanes_.back().id, j.E);
+    } else if (c.kind == GROW) {
+        Lane &l = lanes_[c.index];
+        sumL_ += j.E - l.size;
+        l.size = j.E;
+        stats.lanes_moved += lanes_.size() - 1 - c.index;
+        log(SALUS_EV_LANE_GROW, l.id, l.size);
+    }
+    Lane &l = lanes_[c.index];
+    l.ref += 1;
+    j.lane = l.id;
+    if (int rc = place(j, floor())) return rc;
+    j.state = SALUS_JOB_RESIDENT;
+    sumP_ += j.P;
+    j.admit_round = round_;
+    stats.admitted += 1;
+    log(SALUS_EV_ADMIT, j.id, l.id);
+    return SALUS_OK;
+}
+
+int PoolCore::evict(Job &j, bool automatic, void *pinned)
+{
+    if (dev_->present()) {
+        if (pinned) {
+            if (j.host && j.host_owned) dev_->pinned_free(j.host);
+            j.host = pinned;
+            j.host_owned = false;
+        } else if (!j.host || !j.host_owned) {
+            j.host = dev_->pinned_alloc(j.P);
+            j.host_owned = true;
+            if (!j.host) { error = "pinned host allocation failed"; return SALUS_EHIP; }
+        }
+        if (dev_->evict(j.host, j.off, j.P)) { error = "device-to-host copy failed"; return SALUS_EHIP; }
+    }
+    blocks_.erase(j.off);
+    sumP_ -= j.P;
+    j.state = SALUS_JOB_EVICTED;
+    j.auto_evicted = automatic;
+    stats.evictions += 1;
+    stats.bytes_d2h += j.P;
+    log(SALUS_EV_EVICT, j.id, j.P);
+    return SALUS_OK;
+}
+
+// ProcessRequests of Algorithm 1, plus priority admission (Section 4.2).
+void PoolCore::process_requests()
+{
+    std::vector<int32_t> waiting(queue_.begin(), queue_.end());
+    for (int32_t id : waiting) {
+        Job &j = jobs_[id];
+        Choice c = find_lane(j.P, j.E, sumP_);
+        if (c.kind == NONE && policy_ == SALUS_POLICY_PRIORITY) {
+            // candidates: strictly lower priority; lowest priority first, then
+            // largest persistent state, then youngest
+            std::vector<int32_t> victims;
+            for (const Job &v : jobs_)
+                if (v.state == SALUS_JOB_RESIDENT && v.priority < j.priority) victims.push_back(v.id);
+            std::sort(victims.begin(), victims.end(), [&](int32_t a, int32_t b) {
+                const Job &x = jobs_[a], &y = jobs_[b];
+                if (x.priority != y.priority) return x.priority < y.priority;
+                if (x.P != y.P) return x.P > y.P;
+                return x.id > y.id;
+            });
+            uint64_t left = sumP_;
+            size_t need = 0;
+            for (size_t n = 0; n < victims.size(); ++n) {
+                left -= jobs_[victims[n]].P;
+                if (find_lane(j.P, j.E, left).kind != NONE) { need = n + 1; break; }
+            }
+            for (size_t n = 0; n < need; ++n)
+                if (evict(jobs_[victims[n]], true, nullptr)) return;
+            if (need) c = find_lane(j.P, j.E, sumP_);
+        }
+        if (c.kind != NONE) {
+            queue_.erase(std::find(queue_.begin(), queue_.end(), id));
+            if (admit(j, c)) return;
+        }
+    }
+}
+
+int32_t PoolCore::arrive(uint64_t P, uint64_t E, int32_t priority, uint64_t pending, int32_t *job)
+{
+    if (job) *job = -1;
+    if (P == 0 || E == 0) { error = "P and E must be positive"; return SALUS_EINVAL; }
+    P = round_up(P, A_);
+    E = round_up(E, A_);
+    if (P + E > C_ || P + E < P) { error = "P + E exceeds the pool capacity"; return SALUS_ENEVER; }
+    Job j;
+    j.id = (int32_t)jobs_.size();
+    j.P = P;
+    j.E = E;
+    j.priority = priority;
+    j.pending = pending;
+    j.arrival_round = round_;
+    jobs_.push_back(j);
+    queue_.push_back(j.id);
+    error.clear();
+    process_requests();
+    if (job) *job = j.id;
+    if (!error.empty()) return SALUS_EHIP;
+    return jobs_[j.id].state == SALUS_JOB_RESIDENT ? SALUS_OK : SALUS_QUEUED;
+}
+
+int32_t PoolCore::finish(int32_t id)
+{
+    if (id < 0 || (size_t)id >= jobs_.size() || jobs_[id].state == SALUS_JOB_DONE) {
+        error = "no such live job";
+        return SALUS_EINVAL;
+    }
+    Job &j = jobs_[id];
+    if (j.state == SALUS_JOB_QUEUED) {
+        queue_.erase(std::find(queue_.begin(), queue_.end(), id));
+        j.state = SALUS_JOB_DONE;
+        return SALUS_OK;
+    }
+    if (j.state == SALUS_JOB_RESIDENT) {
+        blocks_.erase(j.off);
+        sumP_ -= j.P;
+    }
+    if (j.host && j.host_owned) dev_->pinned_free(j.host);
+    j.host = nullptr;
+    j.state = SALUS_JOB_DONE;
+    for (size_t i = 0; i < lanes_.size(); ++i) {
+        if (lanes_[i].id != j.lane) continue;
+        if (--lanes_[i].ref == 0) {
+            uint64_t behind = lanes_.size() - 1 - i;
+            sumL_ -= lanes_[i].size;
+            log(SALUS_EV_LANE_DEL, lanes_[i].id, 0);
+            lanes_.erase(lanes_.begin() + i);
+            stats.lanes_deleted += 1;
+            if (behind) {   // younger lanes slide: bookkeeping only
+                stats.lanes_moved += behind;
+                log(SALUS_EV_LANE_MOVED, behind, 0);
+            }
+        }
+        break;
+    }
+    error.clear();
+    process_requests();
+    for (size_t v = 0; v < jobs_.size(); ++v)
+        if (jobs_[v].state == SALUS_JOB_EVICTED && jobs_[v].auto_evicted &&
+            sumP_ + jobs_[v].P + sumL_ <= C_)
+            if (switch_in((int32_t)v)) break;
+    return error.empty() ? SALUS_OK : SALUS_EHIP;
+}
+
+int32_t PoolCore::switch_out(int32_t id, void *pinned)
+{
+    if (id < 0 || (size_t)id >= jobs_.size()) { error = "no such job"; return SALUS_EINVAL; }
+    if (jobs_[id].state != SALUS_JOB_RESIDENT) { error = "job is not resident"; return SALUS_ENOTRESIDENT; }
+    return evict(jobs_[id], false, pinned);
+}
+
+int32_t PoolCore::switch_in(int32_t id)
+{
+    if (id < 0 || (size_t)id >= jobs_.size() || jobs_[id].state != SALUS_JOB_EVICTED) {
+        error = "job is not evicted";
+        return SALUS_EINVAL;
+    }
+    Job &j = jobs_[id];
+    if (sumP_ + j.P + sumL_ > C_) { error = "no room to restore the job"; return SALUS_ENOMEM; }
+    if (int rc = place(j, floor())) return rc;
+    j.state = SALUS_JOB_RESIDENT;
+    j.auto_evicted = false;
+    sumP_ += j.P;
+    if (dev_->present() && dev_->restore(j.off, j.host, j.P)) {
+        error = "host-to-device copy failed";
+        return SALUS_EHIP;
+    }
+    if (!j.host_owned) j.host = nullptr;    // the caller's buffer is released; ours stays cached
+    stats.restores += 1;
+    stats.bytes_h2d += j.P;
+    log(SALUS_EV_RESTORE, j.id, j.off);
+    return SALUS_OK;
+}
+
+int32_t PoolCore::set_pending(int32_t id, uint64_t n)
+{
+    if (id < 0 || (size_t)id >= jobs_.size() || jobs_[id].state == SALUS_JOB_DONE) {
+        error = "no such live job";
+        return SALUS_EINVAL;
+    }
+    jobs_[id].pending = n;
+    return SALUS_OK;
+}
+
+int32_t PoolCore::query(int32_t id, salus_job_info *o) const
+{
+    if (id < 0 || (size_t)id >= jobs_.size() || !o) return SALUS_EINVAL;
+    const Job &j = jobs_[id];
+    o->state = j.state;
+    o->lane = j.lane;
+    o->priority = j.priority;
+    o->auto_evicted = j.auto_evicted;
+    o->P = j.P;
+    o->E = j.E;
+    o->persist_off = j.state == SALUS_JOB_RESIDENT ? j.off : UINT64_MAX;
+    o->lane_off = UINT64_MAX;
+    o->lane_size = 0;
+    if (j.state == SALUS_JOB_RESIDENT || j.state == SALUS_JOB_EVICTED)
+        o->lane_off = lane_base(j.lane, &o->lane_size);
+    o->pending = j.pending;
+    o->served = j.served;
+    o->arrival_round = j.arrival_round;
+    o->admit_round = j.admit_round;
+    return SALUS_OK;
+}
+
+// One round: at most one job per lane (iterations are serialized within a lane
+// and parallel across lanes, Section 3.3), switching only between iterations
+// (Section 3.2.2), under the policies of Section 4.
+int32_t PoolCore::schedule(salus_slot *out, uint32_t cap, uint32_t *n)
+{
+    if (!n || (!out && cap)) return SALUS_EINVAL;
+    if (cap < lanes_.size()) { error = "slot array smaller than the number of lanes"; return SALUS_EINVAL; }
+    // best runnable job per lane id in one pass over the jobs
+    std::map<int32_t, int32_t> best;    // lane id -> job id
+    auto better = [&](const Job &a, const Job &b) {
+        switch (policy_) {
+        case SALUS_POLICY_FAIR:
+            return a.served != b.served ? a.served < b.served : a.id < b.id;
+        case SALUS_POLICY_PRIORITY:
+            if (a.priority != b.priority) return a.priority > b.priority;
+            if (a.pending != b.pending) return a.pending < b.pending;
+            return a.id < b.id;
+        default:
+            return a.id < b.id;
+        }
+    };
+    for (const Job &j : jobs_) {
+        if (j.state != SALUS_JOB_RESIDENT || j.pending == 0) continue;
+        auto it = best.find(j.lane);
+        if (it == best.end()) best[j.lane] = j.id;
+        else if (better(j, jobs_[it->second])) it->second = j.id;
+    }
+    uint32_t k = 0;
+    if (policy_ == SALUS_POLICY_FIFO) {
+        int32_t pick = -1;
+        for (const auto &kv : best)
+            if (pick < 0 || kv.second < pick) pick = kv.second;
+        if (pick >= 0) out[k++] = {pick, jobs_[pick].lane};
+    } else {
+        for (const Lane &l : lanes_) {
+            auto it = best.find(l.id);
+            if (it != best.end()) out[k++] = {it->second, l.id};
+        }
+    }
+    for (uint32_t i = 0; i < k; ++i) {
+        jobs_[out[i].job].served += 1;
+        jobs_[out[i].job].pending -= 1;
+    }
+    *n = k;
+    round_ += 1;
+    stats.rounds += 1;
+    stats.iterations += k;
+    return SALUS_OK;
+}
+
+}  // namespace salus

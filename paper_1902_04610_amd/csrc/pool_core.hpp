@@ -1,0 +1,105 @@
+// Host side of the pool: persistent-region allocator, lane assignment
+// (Algorithm 1 of the Salus paper), safety condition (Section 3.3.2),
+// iteration scheduler (Section 4) and the planners for switching and
+// compaction.  Pure C++, no GPU calls: data movement goes through DeviceOps.
+#pragma once
+#include <cstdint>
+#include <deque>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "salus.h"
+
+namespace salus {
+
+// What the host logic needs from the device side.  Offsets are relative to the
+// pool base.  Every call is complete (synchronised) when it returns 0.
+struct DeviceOps {
+    virtual ~DeviceOps() {}
+    virtual bool present() const = 0;                       // false: metadata-only pool
+    virtual int evict(void *host, uint64_t off, uint64_t n) = 0;      // device -> host
+    virtual int restore(uint64_t off, const void *host, uint64_t n) = 0;
+    // moves in ascending address order, every dst below its src; [free_off,
+    // free_off + free_len) lies above all live blocks and may be used as staging
+    // (ephemeral memory is dead between iterations, Section 3.2.2)
+    virtual int slide(const salus_move *moves, uint32_t n, uint64_t free_off, uint64_t free_len) = 0;
+    virtual void *pinned_alloc(uint64_t n) = 0;
+    virtual void pinned_free(void *p) = 0;
+};
+
+struct Job {
+    int32_t id = -1;
+    uint64_t P = 0, E = 0;
+    int32_t priority = 0;
+    uint64_t pending = 0, served = 0;
+    int32_t state = SALUS_JOB_QUEUED;
+    int32_t lane = -1;
+    uint64_t off = 0;
+    bool auto_evicted = false;
+    void *host = nullptr;        // evicted bytes, or a cached pinned buffer
+    bool host_owned = false;     // allocated by the library
+    uint64_t arrival_round = 0, admit_round = UINT64_MAX;
+};
+
+struct Lane {
+    int32_t id;
+    uint64_t size;               // L_j
+    uint32_t ref;                // jobs assigned to the lane
+};
+
+class PoolCore {
+public:
+    PoolCore(uint64_t capacity, uint64_t granule, uint32_t max_lanes, int32_t policy,
+             DeviceOps *dev);
+    ~PoolCore();
+
+    int32_t arrive(uint64_t P, uint64_t E, int32_t priority, uint64_t pending, int32_t *job);
+    int32_t finish(int32_t job);
+    int32_t set_pending(int32_t job, uint64_t n);
+    int32_t query(int32_t job, salus_job_info *out) const;
+    int32_t schedule(salus_slot *out, uint32_t cap, uint32_t *n);
+    int32_t switch_out(int32_t job, void *pinned);
+    int32_t switch_in(int32_t job);
+    int32_t compact(std::vector<salus_move> *plan);
+
+    const Job *job(int32_t id) const {
+        return (id >= 0 && (size_t)id < jobs_.size()) ? &jobs_[id] : nullptr;
+    }
+    uint64_t lane_base(int32_t lane_id, uint64_t *size = nullptr) const;
+    const std::vector<Lane> &lanes() const { return lanes_; }
+    uint64_t capacity() const { return C_; }
+    uint64_t floor() const { return C_ - sumL_; }
+    uint64_t queued() const { return queue_.size(); }
+
+    salus_stats stats{};
+    std::vector<salus_event> events;
+    std::string error;
+
+private:
+    enum Kind { NONE, NEW, USE, GROW };
+    struct Choice { Kind kind = NONE; size_t index = 0; };
+
+    Choice find_lane(uint64_t P, uint64_t E, uint64_t residentP) const;
+    void process_requests();
+    int admit(Job &j, Choice c);
+    int place(Job &j, uint64_t fl);
+    bool first_fit(uint64_t P, uint64_t fl, uint64_t *off) const;
+    int evict(Job &j, bool automatic, void *pinned);
+    int do_compact(std::vector<salus_move> *plan);
+    void log(int32_t kind, uint64_t a, uint64_t b) { events.push_back({kind, 0, a, b}); }
+
+    uint64_t C_, A_;
+    uint32_t max_lanes_;
+    int32_t policy_;
+    DeviceOps *dev_;
+    std::vector<Job> jobs_;
+    std::vector<Lane> lanes_;             // creation order == address order from the top
+    std::deque<int32_t> queue_;           // Q of Algorithm 1
+    std::map<uint64_t, int32_t> blocks_;  // live persistent blocks: offset -> job
+    uint64_t sumP_ = 0, sumL_ = 0;        // over resident jobs / over lanes
+    int32_t next_lane_ = 0;
+    uint64_t round_ = 0;
+};
+
+}  // namespace salus

@@ -1,0 +1,267 @@
+"""Thin ctypes binding of libsalus.so (C ABI in include/salus.h).
+
+Argument marshalling only: every step of the path runs inside the library.
+There is no fallback: if the library is missing, loading raises.
+"""
+import ctypes as C
+import os
+
+import torch  # noqa: F401  (first, so that the HIP runtime already loaded by torch is the one the library binds to)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsalus.so")
+
+OK, QUEUED = 0, 1
+EINVAL, ENOMEM, ENOTRESIDENT, EBUSY, ENEVER, EHIP = -1, -2, -3, -4, -5, -6
+POLICY_FIFO, POLICY_FAIR, POLICY_PRIORITY, POLICY_PACK = 0, 1, 2, 3
+JOB_QUEUED, JOB_RESIDENT, JOB_EVICTED, JOB_DONE = 0, 1, 2, 3
+ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
+F32, BF16 = 0, 1
+COPY_KERNEL, COPY_DMA = 0, 1
+
+
+class Config(C.Structure):
+    _fields_ = [("granule", C.c_uint64), ("max_lanes", C.c_uint32), ("policy", C.c_int32),
+                ("stream", C.c_void_p), ("copy_engine", C.c_int32), ("reserved", C.c_int32)]
+
+
+class JobInfo(C.Structure):
+    _fields_ = [("state", C.c_int32), ("lane", C.c_int32), ("priority", C.c_int32),
+                ("auto_evicted", C.c_int32), ("P", C.c_uint64), ("E", C.c_uint64),
+                ("persist_off", C.c_uint64), ("lane_off", C.c_uint64), ("lane_size", C.c_uint64),
+                ("pending", C.c_uint64), ("served", C.c_uint64),
+                ("arrival_round", C.c_uint64), ("admit_round", C.c_uint64)]
+
+
+class Slot(C.Structure):
+    _fields_ = [("job", C.c_int32), ("lane", C.c_int32)]
+
+
+class Move(C.Structure):
+    _fields_ = [("src", C.c_uint64), ("dst", C.c_uint64), ("len", C.c_uint64)]
+
+
+class Layer(C.Structure):
+    _fields_ = [("K", C.c_uint32), ("N", C.c_uint32), ("w_off", C.c_uint64),
+                ("act", C.c_int32), ("reserved", C.c_int32)]
+
+
+class GemmDesc(C.Structure):
+    _fields_ = [("job", C.c_int32), ("M", C.c_uint32), ("n_layers", C.c_uint32),
+                ("dtype", C.c_int32), ("layers", C.POINTER(Layer)),
+                ("x_off", C.c_uint64), ("y_off", C.c_uint64), ("h_off", C.c_uint64)]
+
+
+class Stats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in (
+        "rounds", "iterations", "bytes_d2h", "bytes_h2d", "bytes_d2d", "moves", "compactions",
+        "lanes_opened", "lanes_deleted", "lanes_moved", "evictions", "restores", "admitted",
+        "queued", "gemm_launches")]
+
+
+class Event(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("pad", C.c_int32), ("a", C.c_uint64), ("b", C.c_uint64)]
+
+
+_PROTOS = {
+    "salus_pool_create": [C.c_void_p, C.c_uint64, C.POINTER(Config), C.POINTER(C.c_void_p)],
+    "salus_pool_destroy": [C.c_void_p],
+    "salus_lane_alloc": [C.c_void_p, C.c_uint64, C.c_uint64, C.c_int32, C.c_uint64,
+                         C.POINTER(C.c_int32)],
+    "salus_lane_free": [C.c_void_p, C.c_int32],
+    "salus_job_query": [C.c_void_p, C.c_int32, C.POINTER(JobInfo)],
+    "salus_job_set_pending": [C.c_void_p, C.c_int32, C.c_uint64],
+    "salus_job_write": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
+    "salus_job_read": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
+    "salus_schedule_iteration": [C.c_void_p, C.POINTER(Slot), C.c_uint32, C.POINTER(C.c_uint32)],
+    "salus_grouped_forward": [C.c_void_p, C.POINTER(GemmDesc), C.c_uint32, C.c_void_p],
+    "salus_switch_out": [C.c_void_p, C.c_int32, C.c_void_p],
+    "salus_switch_in": [C.c_void_p, C.c_int32],
+    "salus_compact": [C.c_void_p, C.POINTER(Move), C.c_uint32, C.POINTER(C.c_uint32)],
+    "salus_get_stats": [C.c_void_p, C.POINTER(Stats)],
+    "salus_poll_events": [C.c_void_p, C.POINTER(Event), C.c_uint32, C.POINTER(C.c_uint32)],
+    "salus_lanes": [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_uint64), C.POINTER(C.c_uint64),
+                    C.c_uint32, C.POINTER(C.c_uint32)],
+    "salus_last_error": [C.c_void_p],
+    "salus_scan_u64": [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p],
+    "salus_fill_pattern": [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p],
+    "salus_check_pattern": [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.POINTER(C.c_uint64),
+                            C.c_void_p],
+    "salus_copy": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p],
+}
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_1902_04610_amd.build` "
+                "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        for name, args in _PROTOS.items():
+            fn = getattr(L, name)
+            fn.argtypes = args
+            fn.restype = C.c_char_p if name == "salus_last_error" else C.c_int32
+        _lib = L
+    return _lib
+
+
+class SalusError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"salus error {code}: {msg}")
+        self.code = code
+
+
+class Pool:
+    """One pool = one caller-owned device range.  Methods mirror the C calls
+    one to one and return plain Python values."""
+
+    def __init__(self, base_ptr, capacity, granule=256, max_lanes=0, policy=POLICY_FAIR,
+                 stream=None, copy_engine=COPY_KERNEL):
+        self._lib = lib()
+        cfg = Config(granule, max_lanes, policy, stream, copy_engine, 0)
+        h = C.c_void_p()
+        rc = self._lib.salus_pool_create(base_ptr, capacity, C.byref(cfg), C.byref(h))
+        if rc != OK:
+            raise SalusError(rc, "salus_pool_create rejected its arguments")
+        self._h = h
+        self.capacity = capacity
+
+    def close(self):
+        if self._h:
+            self._lib.salus_pool_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc, allowed=(OK,)):
+        if rc not in allowed:
+            raise SalusError(rc, (self._lib.salus_last_error(self._h) or b"").decode())
+        return rc
+
+    def last_error(self):
+        return (self._lib.salus_last_error(self._h) or b"").decode()
+
+    # -- Algorithm 1 ---------------------------------------------------------
+    def lane_alloc(self, P, E, priority=0, pending=0):
+        """Returns (status, job id); status may be OK, QUEUED, ENEVER or EINVAL."""
+        job = C.c_int32(-1)
+        rc = self._lib.salus_lane_alloc(self._h, P, E, priority, pending, C.byref(job))
+        self._check(rc, (OK, QUEUED, ENEVER, EINVAL))
+        return rc, job.value
+
+    def lane_free(self, job):
+        return self._lib.salus_lane_free(self._h, job)
+
+    def job_query(self, job):
+        info = JobInfo()
+        self._check(self._lib.salus_job_query(self._h, job, C.byref(info)))
+        return info
+
+    def job_set_pending(self, job, n):
+        return self._lib.salus_job_set_pending(self._h, job, n)
+
+    def job_write(self, job, off, host_ptr, nbytes):
+        self._check(self._lib.salus_job_write(self._h, job, off, host_ptr, nbytes))
+
+    def job_read(self, job, off, host_ptr, nbytes):
+        self._check(self._lib.salus_job_read(self._h, job, off, host_ptr, nbytes))
+
+    def lanes(self):
+        n = C.c_uint32()
+        self._lib.salus_lanes(self._h, None, None, None, 0, C.byref(n))
+        k = n.value
+        ids, offs, sizes = (C.c_int32 * k)(), (C.c_uint64 * k)(), (C.c_uint64 * k)()
+        self._lib.salus_lanes(self._h, ids, offs, sizes, k, C.byref(n))
+        return [(ids[i], offs[i], sizes[i]) for i in range(k)]
+
+    # -- scheduling ------------------------------------------------------------
+    def schedule_iteration(self, cap=256):
+        slots = (Slot * cap)()
+        n = C.c_uint32()
+        self._check(self._lib.salus_schedule_iteration(self._h, slots, cap, C.byref(n)))
+        return [(slots[i].job, slots[i].lane) for i in range(n.value)]
+
+    # -- packed iteration --------------------------------------------------------
+    @staticmethod
+    def make_descs(items):
+        """items: iterable of dicts(job, M, dtype, layers=[(K, N, w_off, act)], x_off, y_off,
+        h_off).  Returns (array, keepalive) ready for grouped_forward."""
+        items = list(items)
+        arr = (GemmDesc * len(items))()
+        keep = []
+        for i, it in enumerate(items):
+            L = (Layer * len(it["layers"]))(*[Layer(K, N, w, a, 0) for (K, N, w, a) in it["layers"]])
+            keep.append(L)
+            arr[i] = GemmDesc(it["job"], it["M"], len(it["layers"]), it["dtype"], L,
+                              it["x_off"], it["y_off"], it.get("h_off", 0))
+        return arr, keep
+
+    def grouped_forward(self, descs, n=None, stream=None):
+        if n is None:
+            n = len(descs)
+        return self._check(self._lib.salus_grouped_forward(self._h, descs, n, stream),
+                           (OK, EINVAL, ENOTRESIDENT, EBUSY))
+
+    # -- switching -----------------------------------------------------------------
+    def switch_out(self, job, pinned_ptr=None):
+        return self._lib.salus_switch_out(self._h, job, pinned_ptr)
+
+    def switch_in(self, job):
+        return self._lib.salus_switch_in(self._h, job)
+
+    def compact(self, cap=4096):
+        plan = (Move * cap)()
+        n = C.c_uint32()
+        self._check(self._lib.salus_compact(self._h, plan, cap, C.byref(n)))
+        return [(plan[i].src, plan[i].dst, plan[i].len) for i in range(min(n.value, cap))]
+
+    # -- introspection ----------------------------------------------------------------
+    def stats(self):
+        s = Stats()
+        self._lib.salus_get_stats(self._h, C.byref(s))
+        return {n: getattr(s, n) for n, _ in Stats._fields_}
+
+    def poll_events(self, cap=65536):
+        ev = (Event * cap)()
+        n = C.c_uint32()
+        self._lib.salus_poll_events(self._h, ev, cap, C.byref(n))
+        return [(ev[i].kind, ev[i].a, ev[i].b) for i in range(n.value)]
+
+
+def scan_u64(values, scratch_ptr, stream=None):
+    n = len(values)
+    a = (C.c_uint64 * n)(*values)
+    out = (C.c_uint64 * (n + 1))()
+    rc = lib().salus_scan_u64(a, n, out, scratch_ptr, stream)
+    if rc != OK:
+        raise SalusError(rc, "salus_scan_u64")
+    return list(out)
+
+
+def fill_pattern(dev_ptr, nbytes, seed, stream=None):
+    rc = lib().salus_fill_pattern(dev_ptr, nbytes, seed, stream)
+    if rc != OK:
+        raise SalusError(rc, "salus_fill_pattern")
+
+
+def check_pattern(dev_ptr, nbytes, seed, scratch_ptr, stream=None):
+    bad = C.c_uint64()
+    rc = lib().salus_check_pattern(dev_ptr, nbytes, seed, scratch_ptr, C.byref(bad), stream)
+    if rc != OK:
+        raise SalusError(rc, "salus_check_pattern")
+    return bad.value
+
+
+def copy(dst_ptr, src_ptr, nbytes, stream=None):
+    rc = lib().salus_copy(dst_ptr, src_ptr, nbytes, stream)
+    if rc != OK:
+        raise SalusError(rc, "salus_copy")

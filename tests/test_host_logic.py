@@ -1,0 +1,143 @@
+"""CPU-only checks of the library's host logic.
+
+With a NULL base the pool is metadata-only: allocator, lane assignment,
+scheduler, eviction decisions and compaction plans run exactly as on the GPU
+but nothing is copied.  Every observable (status codes, offsets, lane bases,
+schedules, event log, counters, move plans) must equal the oracle's, bit for bit.
+"""
+import os
+import random
+import re
+
+import pytest
+
+from oracle import pool as op
+from paper_1902_04610_amd import salus
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "salus.h")).read()
+    declared = set(re.findall(r"\b(salus_[a-z0-9_]+)\s*\(", text))
+    assert {"salus_pool_create", "salus_lane_alloc", "salus_lane_free", "salus_schedule_iteration",
+            "salus_grouped_forward", "salus_switch_out", "salus_switch_in",
+            "salus_compact"} <= declared
+    L = salus.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(salus._PROTOS)        # the binding covers the whole header
+
+
+def snapshot_oracle(p):
+    jobs = []
+    for j in p.jobs:
+        in_lane = j.state in (op.RESIDENT, op.EVICTED)
+        jobs.append((j.state, j.lane if j.state != op.QUEUED else -1, j.P, j.E,
+                     j.off if j.state == op.RESIDENT else None,
+                     p.lane_base(j.lane) if in_lane else None,
+                     p.lane_by_id(j.lane).size if in_lane else 0,
+                     j.pending, j.served, int(j.auto_evicted and j.state == op.EVICTED)))
+    lanes = [(l.id, p.lane_base(l.id), l.size) for l in p.lanes]
+    return jobs, lanes
+
+
+def snapshot_lib(p, njobs):
+    jobs = []
+    for i in range(njobs):
+        q = p.job_query(i)
+        in_lane = q.state in (salus.JOB_RESIDENT, salus.JOB_EVICTED)
+        jobs.append((q.state, q.lane if q.state != salus.JOB_QUEUED else -1, q.P, q.E,
+                     q.persist_off if q.state == salus.JOB_RESIDENT else None,
+                     q.lane_off if in_lane else None, q.lane_size, q.pending, q.served,
+                     int(q.auto_evicted and q.state == salus.JOB_EVICTED)))
+    return jobs, p.lanes()
+
+
+STAT_KEYS = ("rounds", "iterations", "bytes_d2h", "bytes_h2d", "bytes_d2d", "moves", "compactions",
+             "lanes_opened", "lanes_deleted", "lanes_moved", "evictions", "restores", "admitted")
+
+
+def drive_both(seed, steps, C, granule, max_lanes, policy, size_hi):
+    rnd = random.Random(seed)
+    o = op.Pool(C, granule=granule, max_lanes=max_lanes, policy=policy)
+    g = salus.Pool(None, C, granule=granule, max_lanes=max_lanes, policy=policy)
+    for step in range(steps):
+        r = rnd.random()
+        alive = [j.id for j in o.jobs if j.state != op.DONE]
+        if r < 0.40 or not alive:
+            P, E = rnd.randint(1, size_hi), rnd.randint(1, size_hi)
+            pr, pend = rnd.randint(0, 3), rnd.randint(0, 12)
+            so, jo = o.job_arrive(P, E, pr, pend)
+            sg, jg = g.lane_alloc(P, E, pr, pend)
+            assert (so, jo) == (sg, jg), (seed, step)
+        elif r < 0.65:
+            jid = rnd.choice(alive + [len(o.jobs) + 3])
+            assert o.job_finish(jid) == g.lane_free(jid), (seed, step)
+        elif r < 0.85:
+            assert o.schedule_iteration() == g.schedule_iteration(), (seed, step)
+        elif r < 0.90:
+            jid = rnd.choice(alive)
+            n = rnd.randint(0, 9)
+            assert o.set_pending(jid, n) == g.job_set_pending(jid, n)
+        elif r < 0.96:
+            jid = rnd.choice(alive)
+            if o.jobs[jid].state == op.EVICTED:
+                assert o.switch_in(jid) == g.switch_in(jid), (seed, step)
+            else:
+                assert o.switch_out(jid) == g.switch_out(jid), (seed, step)
+        else:
+            assert o.compact() == g.compact(), (seed, step)
+        o.check_invariants()
+        assert snapshot_oracle(o) == snapshot_lib(g, len(o.jobs)), (seed, step)
+        assert [tuple(e) for e in o.events] == g.poll_events(), (seed, step)
+        o.events.clear()
+        st = g.stats()
+        assert {k: o.stats[k] for k in STAT_KEYS} == {k: st[k] for k in STAT_KEYS}, (seed, step)
+        assert st["queued"] == len(o.Q)
+    g.close()
+
+
+@pytest.mark.parametrize("policy", [op.FIFO, op.RR, op.PRIORITY, op.PACK])
+def test_random_event_sequences_match_oracle(policy):
+    for seed in range(12):
+        drive_both(seed * 7 + policy, 250, C=64 * 1024, granule=256,
+                   max_lanes=[0, 2, 6][seed % 3], policy=policy, size_hi=12000)
+
+
+def test_tight_pool_with_many_compactions_matches_oracle():
+    for seed in range(8):
+        drive_both(100 + seed, 400, C=16 * 1024, granule=16, max_lanes=3, policy=op.RR, size_hi=2500)
+
+
+def test_workload1_layout_through_the_library():
+    MiB = 1 << 20
+    g = salus.Pool(None, 4 * MiB, granule=256, policy=salus.POLICY_FAIR)
+    for _ in range(4):
+        assert g.lane_alloc(512 * 1024, MiB, 0, 8)[0] == salus.OK
+    rows = [ln.split() for ln in open(os.path.join(ROOT, "tests", "golden", "workload1_layout.txt"))
+            if ln.strip() and ln[0] != "#"]
+    for job, lane, base, size, off in (map(int, r) for r in rows):
+        q = g.job_query(job)
+        assert (q.lane, q.lane_off, q.lane_size, q.persist_off) == (lane, base, size, off)
+    assert [g.schedule_iteration() for _ in range(4)] == [[(0, 0), (1, 1)], [(2, 0), (3, 1)]] * 2
+
+
+def test_error_paths_need_no_gpu():
+    g = salus.Pool(None, 1 << 20)
+    assert g.lane_alloc(1 << 20, 1 << 20)[0] == salus.ENEVER
+    assert g.lane_alloc(0, 5)[0] == salus.EINVAL
+    st, j = g.lane_alloc(4096, 4096, 0, 1)
+    assert st == salus.OK
+    assert g.lane_free(99) == salus.EINVAL
+    assert g.switch_in(j) == salus.EINVAL             # not evicted
+    assert g.switch_out(j) == salus.OK
+    assert g.switch_out(j) == salus.ENOTRESIDENT
+    assert g.schedule_iteration() == []                # evicted jobs are not runnable
+    descs, keep = salus.Pool.make_descs([dict(job=j, M=1, dtype=salus.F32,
+                                              layers=[(4, 4, 0, 0)], x_off=0, y_off=256)])
+    assert g.grouped_forward(descs) == salus.EINVAL   # no device memory behind this pool
+    assert g.lane_free(j) == salus.OK
+    assert g.lane_free(j) == salus.EINVAL              # double free
+    with pytest.raises(salus.SalusError):
+        salus.Pool(None, 1000, granule=48)             # granule must be a power of two
