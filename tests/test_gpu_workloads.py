@@ -1,0 +1,309 @@
+"""End-to-end GPU parity on the synthetic workloads (oracle-sized versions).
+
+Every test drives the library and the CPU oracle with the same events and the
+same seeded inputs.  Schedules, offsets, lane assignments, event logs and all
+copied bytes must be identical; dense-layer outputs must agree within the
+tolerances of test_gpu_kernels.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dense
+from oracle import pool as op
+from paper_1902_04610_amd import salus, synth
+from gpu_util import DevicePool, mlp_layout, norm_rel_err
+from test_gpu_kernels import TOL_BF16, TOL_BF16_TIGHT, TOL_F32
+
+pytestmark = pytest.mark.gpu
+MiB = 1 << 20
+
+
+def same_layout(o, g):
+    for j in o.jobs:
+        q = g.job_query(j.id)
+        assert q.state == j.state, j.id
+        if j.state == op.RESIDENT:
+            assert q.persist_off == j.off, j.id
+        if j.state in (op.RESIDENT, op.EVICTED):
+            assert (q.lane, q.lane_off, q.lane_size) == (j.lane, o.lane_base(j.lane),
+                                                         o.lane_by_id(j.lane).size), j.id
+
+
+def same_events(o, g):
+    assert [tuple(e) for e in o.events] == g.poll_events()
+    o.events.clear()
+
+
+def same_persistent_bytes(o, dp):
+    for j in o.jobs:
+        if j.state == op.RESIDENT:
+            assert np.array_equal(dp.read(j.off, j.P), o.mem[j.off:j.off + j.P]), j.id
+
+
+# --------------------------------------------------------------------------- workload 1
+def run_workload1(with_switch):
+    w = synth.workload1(seed=0)
+    width, batch = w["width"], w["batch"]
+    dp = DevicePool(w["capacity"], policy=salus.POLICY_FAIR, granule=w["granule"])
+    o = op.Pool(w["capacity"], granule=w["granule"], policy=op.RR,
+                mem=np.zeros(w["capacity"], np.uint8))
+    wbytes = width * width * 4
+    for j in range(w["jobs"]):
+        assert dp.pool.lane_alloc(w["P"], w["E"], 0, w["rounds"] // 2) == o.job_arrive(
+            w["P"], w["E"], 0, w["rounds"] // 2)
+        off = o.jobs[j].off
+        for l in range(2):
+            dp.write(off + l * wbytes, w["W"][j][l])
+            o.mem[off + l * wbytes: off + (l + 1) * wbytes] = w["W"][j][l].view(np.uint8).reshape(-1)
+    same_layout(o, dp.pool)
+    xb = batch * width * 4
+    x_off, y_off, h_off = 0, xb, 2 * xb
+    outputs, errs = [], []
+    for rnd in range(w["rounds"]):
+        sched = o.schedule_iteration()
+        assert dp.pool.schedule_iteration() == sched
+        items, refs = [], []
+        for job, lane in sched:
+            it = o.jobs[job].served - 1
+            X = w["X"][job][it]
+            q = dp.pool.job_query(job)
+            dp.write(q.lane_off + x_off, X)
+            items.append(dict(job=job, M=batch, dtype=salus.F32, x_off=x_off, y_off=y_off, h_off=h_off,
+                              layers=[(width, width, 0, salus.ACT_RELU),
+                                      (width, width, wbytes, salus.ACT_NONE)]))
+            # the oracle reads its weights out of its own pool bytes
+            Ws = [o.mem[o.jobs[job].off + l * wbytes: o.jobs[job].off + (l + 1) * wbytes]
+                  .view(np.float32).reshape(width, width) for l in range(2)]
+            refs.append(dense.mlp_forward_f32(X, Ws, [dense.ACT_RELU, dense.ACT_NONE])[-1])
+        descs, keep = salus.Pool.make_descs(items)
+        assert dp.pool.grouped_forward(descs, stream=dp.stream) == salus.OK
+        dp.sync()
+        for (job, lane), ref in zip(sched, refs):
+            q = dp.pool.job_query(job)
+            Y = dp.read(q.lane_off + y_off, batch * width * 4, np.float32).reshape(batch, width).copy()
+            errs.append(norm_rel_err(Y, ref))
+            outputs.append(Y)
+        if with_switch and rnd == 7:                 # after the eighth round
+            assert dp.pool.switch_out(2) == o.switch_out(2) == op.OK
+            assert dp.pool.job_query(2).state == salus.JOB_EVICTED
+            assert dp.pool.switch_in(2) == o.switch_in(2) == op.OK
+            same_layout(o, dp.pool)
+            assert o.jobs[2].off == MiB              # first fit finds the same hole again
+            same_persistent_bytes(o, dp)
+    same_events(o, dp.pool)
+    st = dp.pool.stats()
+    assert st["gemm_launches"] == 2 * w["rounds"]    # one launch per layer depth per round
+    assert (st["bytes_d2h"], st["bytes_h2d"]) == ((w["P"], w["P"]) if with_switch else (0, 0))
+    dp.close()
+    return outputs, errs
+
+
+def test_workload1_round_robin_with_switch():
+    outs, errs = run_workload1(with_switch=True)
+    assert len(outs) == 32 and max(errs) < TOL_F32, max(errs)
+    plain, _ = run_workload1(with_switch=False)
+    for a, b in zip(outs, plain):
+        assert np.array_equal(a, b)                  # the switch changed nothing, bit for bit
+
+
+# --------------------------------------------------------------------------- workload 2
+@pytest.mark.parametrize("dims", [(264, 1032, 264, 136), (1024, 4096, 1024, 1024)])
+def test_workload2_inference_packing_small(dims):
+    models, rounds = (12, 10) if dims[0] < 1024 else (3, 3)
+    acts = [salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE]
+    W = synth.workload2_weights(seed=1, models=models, dims=dims)
+    rates, arrivals = synth.workload2_arrivals(seed=1, models=models, rounds=rounds)
+    w_offs, P, x_off, y_off, h_off, E = mlp_layout(dims, 2, 32)
+    cap = models * (P + E)
+    dp = DevicePool(cap, policy=salus.POLICY_PACK)
+    o = op.Pool(cap, policy=op.PACK)
+    for m in range(models):
+        assert dp.pool.lane_alloc(P, E, 0, 0) == o.job_arrive(P, E, 0, 0)
+        q = dp.pool.job_query(m)
+        for wl, off in zip(W[m], w_offs):
+            dp.write(q.persist_off + off, wl)
+    same_layout(o, dp.pool)
+    assert len(dp.pool.lanes()) == models            # every model has a lane of its own
+    waiting = np.zeros(models, np.int64)
+    worst = 0.0
+    for rnd in range(rounds):
+        waiting += arrivals[rnd]
+        for m in range(models):
+            o.set_pending(m, int(waiting[m] > 0))
+            dp.pool.job_set_pending(m, int(waiting[m] > 0))
+        sched = o.schedule_iteration()
+        assert dp.pool.schedule_iteration() == sched
+        assert [j for j, _ in sched] == [m for m in range(models) if waiting[m] > 0]
+        items, refs = [], []
+        for job, lane in sched:
+            batch = int(min(waiting[job], 32))
+            waiting[job] -= batch                    # the rest waits for the next round
+            X = synth.workload2_inputs(1, job, rnd, batch, dims[0])
+            q = dp.pool.job_query(job)
+            dp.write(q.lane_off + x_off, X)
+            items.append(dict(job=job, M=batch, dtype=salus.BF16, x_off=x_off, y_off=y_off, h_off=h_off,
+                              layers=[(K, N, off, a) for K, N, off, a in
+                                      zip(dims[:-1], dims[1:], w_offs, acts)]))
+            refs.append(dense.mlp_forward_bf16(X, W[job], acts)[-1])
+        descs, keep = salus.Pool.make_descs(items)
+        assert dp.pool.grouped_forward(descs, stream=dp.stream) == salus.OK
+        dp.sync()
+        for it, ref in zip(items, refs):
+            q = dp.pool.job_query(it["job"])
+            Y = dp.read(q.lane_off + y_off, it["M"] * dims[-1] * 4, np.float32).reshape(it["M"], dims[-1])
+            worst = max(worst, norm_rel_err(Y, ref))
+    assert worst < TOL_BF16 and worst < TOL_BF16_TIGHT, worst
+    assert dp.pool.stats()["gemm_launches"] == 3 * rounds
+    dp.close()
+
+
+# --------------------------------------------------------------------------- workload 4
+@pytest.mark.parametrize("engine", [salus.COPY_KERNEL, salus.COPY_DMA])
+def test_workload4_priority_preemption_scaled(engine):
+    """MiB instead of GB: 20 MiB low-priority state, 2 MiB urgent job, 23 MiB pool."""
+    C, P_low, P_high, E = 23 * MiB, 20 * MiB, 2 * MiB, 2 * MiB
+    dp = DevicePool(C, policy=salus.POLICY_PRIORITY, copy_engine=engine)
+    o = op.Pool(C, policy=op.PRIORITY, mem=np.zeros(C, np.uint8))
+    assert dp.pool.lane_alloc(P_low, E, 0, 10 ** 9) == o.job_arrive(P_low, E, 0, 10 ** 9)
+    state = synth.pattern_bytes(3, P_low)
+    dp.write(o.jobs[0].off, state)
+    o.mem[o.jobs[0].off:o.jobs[0].off + P_low] = state
+    high, done_at = None, None
+    for rnd in range(130):
+        if rnd in (50, 100):
+            assert dp.pool.lane_alloc(P_high, E, 5, 10) == o.job_arrive(P_high, E, 5, 10)
+            high, done_at = len(o.jobs) - 1, rnd + 10
+            assert o.jobs[0].state == op.EVICTED
+            same_layout(o, dp.pool)
+            dp.buf.fill_(0x55)                       # the urgent job may use every byte
+            o.mem[:] = 0x55
+        if rnd == done_at:
+            assert dp.pool.lane_free(high) == o.job_finish(high) == op.OK
+            assert o.jobs[0].state == op.RESIDENT
+            same_layout(o, dp.pool)
+            got = dp.read(o.jobs[0].off, P_low)
+            assert np.array_equal(got, state)        # restored bit for bit
+            assert np.array_equal(got, o.mem[o.jobs[0].off:o.jobs[0].off + P_low])
+        assert dp.pool.schedule_iteration() == o.schedule_iteration()
+    same_events(o, dp.pool)
+    st = dp.pool.stats()
+    assert (st["evictions"], st["restores"], st["bytes_d2h"], st["bytes_h2d"]) == \
+           (2, 2, 2 * P_low, 2 * P_low)
+    dp.close()
+
+
+def test_switch_out_to_caller_pinned_buffer():
+    dp = DevicePool(4 * MiB)
+    st, j = dp.pool.lane_alloc(MiB + 256, MiB, 0, 1)
+    data = synth.pattern_bytes(11, MiB + 256)
+    dp.write(dp.pool.job_query(j).persist_off, data)
+    pinned = torch.empty(MiB + 256, dtype=torch.uint8, pin_memory=True)
+    assert dp.pool.switch_out(j, pinned.data_ptr()) == salus.OK
+    assert np.array_equal(pinned.numpy(), data)      # the evicted bytes are where the caller asked
+    dp.buf.zero_()
+    assert dp.pool.switch_in(j) == salus.OK
+    assert np.array_equal(dp.read(dp.pool.job_query(j).persist_off, MiB + 256), data)
+    dp.close()
+
+
+# --------------------------------------------------------------------------- workload 5
+def job_bytes(jid, n):
+    return synth.pattern_bytes(1000 + jid, n)
+
+
+@pytest.mark.parametrize("capacity_gb,rounds", [(250, 400), (48, 400)])
+def test_workload5_fragmentation_replica(capacity_gb, rounds):
+    """1/1024-scale replica (MB instead of GB) mirrored byte for byte on the host."""
+    scale = 1.0 / 1024
+    C = int(capacity_gb * 1e9 * scale) // 256 * 256
+    trace = synth.workload5_trace(seed=4, rounds=rounds, scale=scale)
+    dp = DevicePool(C, policy=salus.POLICY_FAIR, max_lanes=6)
+    o = op.Pool(C, policy=op.RR, max_lanes=6, mem=np.zeros(C, np.uint8))
+    nxt, life, filled = 0, {}, set()
+    for rnd in range(rounds):
+        while nxt < len(trace) and trace[nxt]["arrive"] <= rnd:
+            t = trace[nxt]
+            so, jo = o.job_arrive(t["P"], t["E"], 0, 10 ** 9)
+            assert dp.pool.lane_alloc(t["P"], t["E"], 0, 10 ** 9) == (so, jo)
+            if jo >= 0:
+                life[jo] = t["life"]
+            nxt += 1
+        for j in o.jobs:                              # departures, oldest first
+            if j.state == op.RESIDENT and rnd - j.admit_round >= life[j.id]:
+                assert dp.pool.lane_free(j.id) == o.job_finish(j.id) == op.OK
+        for j in o.jobs:                              # newly admitted jobs load their state
+            if j.state == op.RESIDENT and j.id not in filled:
+                filled.add(j.id)
+                b = job_bytes(j.id, j.P)
+                o.mem[j.off:j.off + j.P] = b
+                dp.write(j.off, b)
+        assert dp.pool.schedule_iteration() == o.schedule_iteration()
+        if o.events:
+            same_layout(o, dp.pool)
+            compacted = any(e[0] == op.EV_COMPACT and e[1] > 0 for e in o.events)
+            same_events(o, dp.pool)
+            if compacted:
+                same_persistent_bytes(o, dp)
+        o.check_invariants()
+    same_persistent_bytes(o, dp)
+    for j in o.jobs:                                  # and each job still holds its own bytes
+        if j.state == op.RESIDENT:
+            assert np.array_equal(dp.read(j.off, j.P), job_bytes(j.id, j.P))
+    st = dp.pool.stats()
+    assert st["bytes_d2d"] == o.stats["bytes_d2d"] and st["compactions"] == o.stats["compactions"]
+    if capacity_gb == 48:
+        assert st["bytes_d2d"] > 0                    # the tight pool really compacts
+    dp.close()
+
+
+def test_forced_compaction_adversarial_shifts():
+    """Blocks far larger than the holes below them: every move overlaps its own source."""
+    C = 96 * MiB
+    dp = DevicePool(C, max_lanes=1, granule=256)
+    o = op.Pool(C, max_lanes=1, granule=256, mem=np.zeros(C, np.uint8))
+    sizes = [256, 9 * MiB + 256, 512, 17 * MiB, 4096, 33 * MiB + 768, 70000, 5 * MiB]
+    for s in sizes:
+        assert dp.pool.lane_alloc(s, 64 * 1024, 0, 1) == o.job_arrive(s, 64 * 1024, 0, 1)
+    for j in o.jobs:
+        b = job_bytes(j.id, j.P)
+        o.mem[j.off:j.off + j.P] = b
+        dp.write(j.off, b)
+    for victim in (0, 2, 4, 6):                       # free the small blocks: tiny shifts
+        assert dp.pool.lane_free(victim) == o.job_finish(victim)
+    plan = o.compact()
+    assert dp.pool.compact() == plan and len(plan) == 4
+    assert min(s - d for s, d, n in plan) == 256 and max(n for s, d, n in plan) > 33 * MiB
+    same_layout(o, dp.pool)
+    same_persistent_bytes(o, dp)
+    assert dp.pool.compact() == []                    # idempotent
+    dp.close()
+
+
+def test_compaction_direct_pieces_and_degenerate_small_free_space():
+    # shift of 40 MiB under a 100 MiB block: pieces of 40 MiB, each its own launch
+    C = 160 * MiB
+    dp = DevicePool(C, max_lanes=1)
+    o = op.Pool(C, max_lanes=1, mem=np.zeros(C, np.uint8))
+    for s in (40 * MiB, 100 * MiB + 512):
+        assert dp.pool.lane_alloc(s, 4096, 0, 1) == o.job_arrive(s, 4096, 0, 1)
+    b = job_bytes(1, o.jobs[1].P)
+    o.mem[o.jobs[1].off:o.jobs[1].off + o.jobs[1].P] = b
+    dp.write(o.jobs[1].off, b)
+    assert dp.pool.lane_free(0) == o.job_finish(0)
+    assert dp.pool.compact() == o.compact() == [(40 * MiB, 0, 100 * MiB + 512)]
+    same_persistent_bytes(o, dp)
+    dp.close()
+    # almost no free space above the blocks: the shift itself is the only room
+    C = 2 * MiB
+    dp = DevicePool(C, max_lanes=1)
+    o = op.Pool(C, max_lanes=1, mem=np.zeros(C, np.uint8))
+    for s in (4096, C - 4096 - 512):
+        assert dp.pool.lane_alloc(s, 256, 0, 1) == o.job_arrive(s, 256, 0, 1)
+    b = job_bytes(1, o.jobs[1].P)
+    o.mem[o.jobs[1].off:o.jobs[1].off + o.jobs[1].P] = b
+    dp.write(o.jobs[1].off, b)
+    assert dp.pool.lane_free(0) == o.job_finish(0)
+    assert dp.pool.compact() == o.compact() == [(4096, 0, C - 4096 - 512)]
+    same_persistent_bytes(o, dp)
+    dp.close()
