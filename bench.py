@@ -1,0 +1,306 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed-iteration hot path on one MI355X.
+
+Workload = the inference-packing configuration: 64 resident 3-layer MLPs
+(1024 -> 4096 -> 1024 -> 1024, GELU, bf16 weights ~ N(0, 0.02), float
+accumulation), Poisson request arrivals with per-model rates lognormal(0, 1)
+req/s sampled every 4 s tick, requests batched to 1..32 per model and round.
+One step = one scheduling round: pending flags -> salus_schedule_iteration ->
+salus_grouped_forward (one grouped launch per layer depth).  All inputs are in
+HBM before the timed region.
+
+Prints ONE JSON line; `value` is TFLOP/s with flops = 2*M*K*N of the true batch
+sizes.  Extra objects: roofline (HBM-bound weight streaming), saturated (all
+64 models at batch 32), switch (evict / restore / compaction bandwidth) and
+cpu_baseline (the CPU oracle on a bounded sample of the same rounds).
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+DIMS = (1024, 4096, 1024, 1024)
+MODELS = 64
+MAX_BATCH = 32
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+MiB = 1 << 20
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-switch", action="store_true", help="skip the evict/restore/compaction figures")
+    ap.add_argument("--hot-only", action="store_true", help="only the timed packed-iteration loop (for profiling)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (jobs are packed inside one device); "
+                 "--gpus must be 1")
+
+    import numpy as np
+    import torch
+    from paper_1902_04610_amd import salus, synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K_steps, W_steps = args.steps, args.warmup
+    rounds = W_steps + K_steps
+
+    # ---------------------------------------------------------------- set-up (untimed)
+    up = lambda v: (v + 255) // 256 * 256
+    w_sizes = [k * n * 2 for k, n in zip(DIMS[:-1], DIMS[1:])]
+    w_offs = [0, w_sizes[0], w_sizes[0] + w_sizes[1]]
+    P = sum(w_sizes)
+    x_off, y_off = 0, up(MAX_BATCH * DIMS[0] * 2)
+    h_off = y_off + up(MAX_BATCH * DIMS[-1] * 4)
+    E = up(h_off + 2 * up(MAX_BATCH * max(DIMS[1:-1]) * 2))
+    cap = MODELS * (P + E)
+    buf = torch.empty(cap, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    pool = salus.Pool(buf.data_ptr(), cap, policy=salus.POLICY_PACK, stream=stream)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    lane_off = []
+    for m in range(MODELS):
+        st, j = pool.lane_alloc(P, E, 0, 0)
+        assert st == salus.OK and j == m
+        q = pool.job_query(m)
+        lane_off.append(q.lane_off)
+        for (k, n), off in zip(zip(DIMS[:-1], DIMS[1:]), w_offs):
+            w = (torch.randn(k, n, generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+            buf[q.persist_off + off:q.persist_off + off + k * n * 2].copy_(w.view(torch.uint8).reshape(-1))
+        x = torch.randn(MAX_BATCH, DIMS[0], generator=gen, device=dev).to(torch.bfloat16)
+        buf[q.lane_off + x_off:q.lane_off + x_off + x.numel() * 2].copy_(x.view(torch.uint8).reshape(-1))
+    torch.cuda.synchronize()
+
+    rates, arrivals = synth.workload2_arrivals(seed=1, models=MODELS, rounds=rounds)
+    layers = [(k, n, off, act) for (k, n), off, act in
+              zip(zip(DIMS[:-1], DIMS[1:]), w_offs, (salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE))]
+
+    def plan(batches_per_round):
+        """Per round: pending flags and job descriptors, marshalled before the clock starts."""
+        out = []
+        for b in batches_per_round:
+            act = [m for m in range(MODELS) if b[m] > 0]
+            flags = (ctypes.c_uint64 * MODELS)(*[1 if b[m] > 0 else 0 for m in range(MODELS)])
+            descs, keep = salus.Pool.make_descs(
+                dict(job=m, M=int(b[m]), dtype=salus.BF16, layers=layers, x_off=x_off, y_off=y_off,
+                     h_off=h_off) for m in act)
+            out.append((flags, descs, keep, len(act)))
+        return out
+
+    waiting = np.zeros(MODELS, np.int64)
+    batches = []
+    for r in range(rounds):
+        waiting += arrivals[r]
+        b = np.minimum(waiting, MAX_BATCH)
+        waiting -= b
+        batches.append(b)
+    poisson = plan(batches)
+    saturated = plan([np.full(MODELS, MAX_BATCH)] * rounds)
+    job_ids = (ctypes.c_int32 * MODELS)(*range(MODELS))
+    slots = (salus.Slot * MODELS)()
+    mac_per_row = sum(k * n for k, n in zip(DIMS[:-1], DIMS[1:]))
+    act_bytes_per_row = 2 * DIMS[0] + sum(2 * n for n in DIMS[1:-1]) * 2 + 4 * DIMS[-1]
+
+    def run(plans, batches_per_round, label):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(K_steps)]
+
+        def step(r, timed_idx=None):
+            flags, descs, keep, n_act = plans[r]
+            pool.set_pending_many(job_ids, flags, MODELS)
+            n = pool.schedule_into(slots, MODELS)
+            assert n == n_act
+            if timed_idx is not None:
+                ev[timed_idx][0].record()
+            rc = pool.grouped_forward(descs, n_act, stream)
+            assert rc == salus.OK, pool.last_error()
+            if timed_idx is not None:
+                ev[timed_idx][1].record()
+
+        for r in range(W_steps):
+            step(r)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(K_steps):
+            step(W_steps + i, i)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        kernel_ms = sum(a.elapsed_time(b) for a, b in ev)
+        rows = sum(int(b.sum()) for b in batches_per_round[W_steps:])
+        active = sum(int((b > 0).sum()) for b in batches_per_round[W_steps:])
+        flops = 2.0 * mac_per_row * rows
+        alg_bytes = active * P + rows * act_bytes_per_row
+        launches = 3 * K_steps
+        res = dict(tflops=flops / wall / 1e12, ms_per_step=wall / K_steps * 1e3,
+                   kernel_ms_per_launch=kernel_ms / launches,
+                   gbs=alg_bytes / (kernel_ms * 1e-3) / 1e9,
+                   bytes_per_launch=alg_bytes / launches,
+                   mean_active=active / K_steps, mean_batch=rows / max(active, 1))
+        log(f"[{label}] {res}")
+        return res
+
+    log(f"pool {cap / 1e9:.2f} GB, {MODELS} models resident, {rounds} rounds planned")
+    main_res = run(poisson, batches, "poisson")
+    if args.hot_only:
+        sat = None
+        # a plain copy of known size in the same process: scale for profiler byte counters
+        cal = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            salus.copy(cal.data_ptr(), cal.data_ptr() + (1 << 30), 1 << 30, stream)
+        torch.cuda.synchronize()
+        del cal
+    else:
+        sat = run(saturated, [np.full(MODELS, MAX_BATCH)] * rounds, "saturated")
+
+    out = {
+        "metric": "packed grouped-GEMM TFLOP/s (% MFMA peak) + job-switch ms/GB (% HBM BW)",
+        "value": round(main_res["tflops"], 3), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": K_steps, "warmup": W_steps,
+        "ms_per_step": round(main_res["ms_per_step"], 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "inference packing: 64 resident 3-layer MLPs 1024-4096-1024-1024 GELU, "
+                               "bf16 weights, Poisson arrivals (rates lognormal(0,1) req/s, 4 s tick), "
+                               "batch 1-32, PACK policy, one grouped launch per layer depth",
+                   "mean_active_models": round(main_res["mean_active"], 2),
+                   "mean_batch": round(main_res["mean_batch"], 2),
+                   "pct_of_bf16_mfma_peak": round(100 * main_res["tflops"] / MFMA_BF16_PEAK_TFLOPS, 3)},
+        "roofline": {"bound": "hbm", "achieved": round(main_res["gbs"], 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(main_res["gbs"] / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "grouped_dense_bf16",
+                     "avg_launch_ms": round(main_res["kernel_ms_per_launch"], 5),
+                     "algorithmic_bytes_per_launch": int(main_res["bytes_per_launch"])},
+    }
+    if sat:
+        out["saturated"] = {"workload": "same 64 models, every model at batch 32 every round",
+                            "tflops": round(sat["tflops"], 2), "ms_per_step": round(sat["ms_per_step"], 4),
+                            "hbm_gbs": round(sat["gbs"], 1), "hbm_frac": round(sat["gbs"] / HBM_PEAK_GBS, 4),
+                            "pct_of_bf16_mfma_peak": round(100 * sat["tflops"] / MFMA_BF16_PEAK_TFLOPS, 3),
+                            "avg_launch_ms": round(sat["kernel_ms_per_launch"], 5)}
+
+    # ---------------------------------------------------------------- CPU oracle on a sample
+    if not args.no_cpu_baseline and not args.hot_only:
+        from concurrent.futures import ThreadPoolExecutor
+        from oracle import dense
+        dense.lib()
+        cores = min(16, os.cpu_count() or 1)
+        sample_rounds = 2
+        work = []
+        for r in range(W_steps, W_steps + sample_rounds):
+            for m in range(MODELS):
+                if batches[r][m] > 0:
+                    work.append((m, int(batches[r][m])))
+        host_w = {}
+        for m in sorted({m for m, _ in work}):
+            q = pool.job_query(m)
+            blob = buf[q.persist_off:q.persist_off + P].cpu().numpy()
+            host_w[m] = [blob[o:o + s].view(np.uint16).reshape(k, n)
+                         for o, s, (k, n) in zip(w_offs, w_sizes, zip(DIMS[:-1], DIMS[1:]))]
+            host_w[m].append(buf[q.lane_off:q.lane_off + MAX_BATCH * DIMS[0] * 2].cpu().numpy()
+                             .view(np.uint16).reshape(MAX_BATCH, DIMS[0]))
+        acts = [dense.ACT_GELU, dense.ACT_GELU, dense.ACT_NONE]
+
+        def one(item):
+            m, b = item
+            return dense.mlp_forward_bf16(host_w[m][3][:b], host_w[m][:3], acts)[-1]
+
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(cores) as ex:
+            list(ex.map(one, work))
+        cpu_s = time.perf_counter() - t0
+        cpu_flops = 2.0 * mac_per_row * sum(b for _, b in work)
+        out["cpu_baseline"] = {"value": round(cpu_flops / cpu_s / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": cores, "kind": "oracle",
+                               "sample": f"the first {sample_rounds} timed rounds of the same workload "
+                                         f"({len(work)} model forwards, {cpu_flops / 2e9:.2f} GMAC), "
+                                         f"{cpu_s:.1f} s wall on {cores} threads"}
+        log(f"[cpu] {out['cpu_baseline']}")
+    pool.close()
+    del buf
+    torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- switch path
+    if not args.no_switch and not args.hot_only:
+        out["switch"] = switch_figures(torch, salus, stream)
+    print(json.dumps(out), flush=True)
+
+
+def switch_figures(torch, salus, stream):
+    """Evict / restore of one 4 GB job over the host link with both engines and
+    sliding compaction of 24 GB of persistent blocks (best of 3 each)."""
+    GB = 10 ** 9
+    res = {}
+    P = 4 * GB // 256 * 256
+    for name, engine in (("kernel", salus.COPY_KERNEL), ("dma", salus.COPY_DMA)):
+        buf = torch.empty(P + 2 * MiB, dtype=torch.uint8, device="cuda:0")
+        pool = salus.Pool(buf.data_ptr(), P + 2 * MiB, stream=stream, copy_engine=engine)
+        st, j = pool.lane_alloc(P, MiB, 0, 1)
+        salus.fill_pattern(buf.data_ptr(), P, 7, stream)
+        out_ms, in_ms = [], []
+        for rep in range(4):                      # the first repetition allocates the pinned buffer
+            t0 = time.perf_counter()
+            assert pool.switch_out(j) == salus.OK
+            t1 = time.perf_counter()
+            assert pool.switch_in(j) == salus.OK
+            t2 = time.perf_counter()
+            if rep:
+                out_ms.append((t1 - t0) * 1e3)
+                in_ms.append((t2 - t1) * 1e3)
+        scratch = torch.zeros(8, dtype=torch.uint8, device="cuda:0")
+        q = pool.job_query(j)
+        assert salus.check_pattern(buf.data_ptr() + q.persist_off, P, 7, scratch.data_ptr(), stream) == 0
+        res[f"evict_{name}_ms_per_GB"] = round(min(out_ms) / (P / GB), 3)
+        res[f"restore_{name}_ms_per_GB"] = round(min(in_ms) / (P / GB), 3)
+        res[f"evict_{name}_GBs"] = round(P / GB / (min(out_ms) * 1e-3), 2)
+        res[f"restore_{name}_GBs"] = round(P / GB / (min(in_ms) * 1e-3), 2)
+        pool.close()
+        del buf
+        torch.cuda.empty_cache()
+    # compaction: [hole 8 GB][3 blocks of 8 GB] -> slide 24 GB down by 8 GB
+    blk = 8 * GB // 256 * 256
+    cap = 4 * blk + 2 * MiB
+    buf = torch.empty(cap, dtype=torch.uint8, device="cuda:0")
+    best = None
+    for rep in range(3):
+        pool = salus.Pool(buf.data_ptr(), cap, stream=stream, max_lanes=1)
+        ids = [pool.lane_alloc(blk, MiB, 0, 1)[1] for _ in range(4)]
+        for k in (1, 2, 3):
+            salus.fill_pattern(buf.data_ptr() + pool.job_query(ids[k]).persist_off, blk, 100 + k, stream)
+        pool.lane_free(ids[0])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        plan = pool.compact()
+        dt = time.perf_counter() - t0
+        moved = sum(m[2] for m in plan)
+        scratch = torch.zeros(8, dtype=torch.uint8, device="cuda:0")
+        for k in (1, 2, 3):
+            assert salus.check_pattern(buf.data_ptr() + pool.job_query(ids[k]).persist_off, blk, 100 + k,
+                                       scratch.data_ptr(), stream) == 0
+        best = dt if best is None else min(best, dt)
+        pool.close()
+    res["compact_ms_per_GB_moved"] = round(best * 1e3 / (moved / GB), 4)
+    res["compact_hbm_GBs_read_plus_write"] = round(2 * moved / best / 1e9, 1)
+    res["compact_hbm_frac"] = round(2 * moved / best / 1e9 / HBM_PEAK_GBS, 4)
+    res["compact_bytes_moved"] = moved
+    log(f"[switch] {res}")
+    return res
+
+
+if __name__ == "__main__":
+    main()

@@ -169,6 +169,9 @@ int32_t salus_lane_free(salus_pool_t *pool, int32_t job);
 
 int32_t salus_job_query(salus_pool_t *pool, int32_t job, salus_job_info *out);
 int32_t salus_job_set_pending(salus_pool_t *pool, int32_t job, uint64_t n);
+/* The same for count jobs at once (host arrays); stops at the first bad job id. */
+int32_t salus_set_pending_many(salus_pool_t *pool, const int32_t *jobs, const uint64_t *n,
+                               uint32_t count);
 
 /* Copy bytes between host memory and a resident job's persistent block
  * (synchronous; for loading weights and reading them back). */

@@ -171,6 +171,16 @@ int32_t salus_job_set_pending(salus_pool_t *pool, int32_t job, uint64_t n)
     return done(pool, pool->core->set_pending(job, n));
 }
 
+int32_t salus_set_pending_many(salus_pool_t *pool, const int32_t *jobs, const uint64_t *n,
+                               uint32_t count)
+{
+    CHECK_POOL(pool);
+    if (count && (!jobs || !n)) return set_error(pool, SALUS_EINVAL, "null array");
+    for (uint32_t i = 0; i < count; ++i)
+        if (int32_t rc = pool->core->set_pending(jobs[i], n[i])) return done(pool, rc);
+    return SALUS_OK;
+}
+
 static int32_t job_io(salus_pool *pool, int32_t job, uint64_t off, void *host, uint64_t n, bool write)
 {
     const Job *j = pool->core->job(job);

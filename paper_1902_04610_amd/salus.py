@@ -71,6 +71,7 @@ _PROTOS = {
     "salus_lane_free": [C.c_void_p, C.c_int32],
     "salus_job_query": [C.c_void_p, C.c_int32, C.POINTER(JobInfo)],
     "salus_job_set_pending": [C.c_void_p, C.c_int32, C.c_uint64],
+    "salus_set_pending_many": [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_uint64), C.c_uint32],
     "salus_job_write": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
     "salus_job_read": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
     "salus_schedule_iteration": [C.c_void_p, C.POINTER(Slot), C.c_uint32, C.POINTER(C.c_uint32)],
@@ -169,6 +170,10 @@ class Pool:
     def job_set_pending(self, job, n):
         return self._lib.salus_job_set_pending(self._h, job, n)
 
+    def set_pending_many(self, jobs_arr, n_arr, count):
+        """jobs_arr: ctypes int32 array, n_arr: ctypes uint64 array."""
+        return self._lib.salus_set_pending_many(self._h, jobs_arr, n_arr, count)
+
     def job_write(self, job, off, host_ptr, nbytes):
         self._check(self._lib.salus_job_write(self._h, job, off, host_ptr, nbytes))
 
@@ -189,6 +194,12 @@ class Pool:
         n = C.c_uint32()
         self._check(self._lib.salus_schedule_iteration(self._h, slots, cap, C.byref(n)))
         return [(slots[i].job, slots[i].lane) for i in range(n.value)]
+
+    def schedule_into(self, slots, cap):
+        """Allocation-free variant: fills a caller-owned Slot array, returns the count."""
+        n = C.c_uint32()
+        self._check(self._lib.salus_schedule_iteration(self._h, slots, cap, C.byref(n)))
+        return n.value
 
     # -- packed iteration --------------------------------------------------------
     @staticmethod
