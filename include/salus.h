@@ -195,6 +195,44 @@ int32_t salus_schedule_iteration(salus_pool_t *pool, salus_slot *out, uint32_t c
 int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
                               void *stream);
 
+/* One layer of a training job: bf16 working weights and float master weights,
+ * both K x N row-major inside the job's persistent block. */
+typedef struct {
+    uint32_t K, N;
+    uint64_t wb_off;       /* bf16 working copy */
+    uint64_t wm_off;       /* float master weights */
+} salus_train_layer;
+
+/* One job's training step.  Offsets are inside the job's lane.
+ * x: M x K_0 bf16 inputs; labels: M int32 class indices in [0, N_last) (values
+ * outside are clamped); logits: M x N_last float (written); loss: one float
+ * (written, mean cross-entropy); work: scratch of salus_train_work_bytes(). */
+typedef struct {
+    int32_t  job;
+    uint32_t M;
+    uint32_t n_layers;
+    float    lr;
+    const salus_train_layer *layers;   /* host pointer, n_layers entries */
+    uint64_t x_off, labels_off, logits_off, loss_off, work_off;
+} salus_train_desc;
+
+/* Bytes of lane scratch a training step needs: the hidden activations of every
+ * layer (kept for the backward pass) and two gradient buffers. */
+uint64_t salus_train_work_bytes(uint32_t M, const salus_train_layer *layers, uint32_t n_layers);
+
+/* Packed training iteration (Sections 2.1 and 5.2: forward pass, backward pass
+ * and parameter update of many tuning jobs sharing the GPU).  For all n jobs
+ * together, on `stream`, asynchronously:
+ *   H_l = bf16(relu(H_{l-1} . Wb_l)) for hidden layers, logits = H_{L-1} . Wb_L;
+ *   loss and dZ_L = (softmax - onehot) / M;
+ *   for l = L..1:  G = bf16(dZ_l);  dZ_{l-1} = (G . Wb_l^T) * [H_{l-1} > 0];
+ *                  Wm_l <- Wm_l - lr * (H_{l-1}^T . G);  Wb_l <- bf16(Wm_l)
+ * with one grouped launch per layer and phase (forward, loss, input gradient,
+ * weight update).  ReLU between layers, no biases, plain SGD.  Same residency,
+ * lane and bounds rules as salus_grouped_forward; K and N multiples of 8. */
+int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *descs, uint32_t n,
+                                 void *stream);
+
 /* Efficient job switching made explicit for jobs that cannot stay
  * (Sections 3.2 and 4.2): RESIDENT -> EVICTED copies the persistent block to
  * pinned host memory and frees it.  pinned_or_null: caller-owned pinned,

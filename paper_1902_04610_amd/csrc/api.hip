@@ -284,7 +284,7 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
                 if (d.dtype != dt || l >= d.n_layers) continue;
                 const salus_layer &L = d.layers[l];
                 const bool last = l + 1 == d.n_layers;
-                Problem pr;
+                Problem pr{};
                 pr.W = res[i].w + L.w_off;
                 pr.X = l == 0 ? res[i].x : res[i].h + ((l - 1) & 1) * res[i].hstride;
                 pr.Y = last ? res[i].y : res[i].h + (l & 1) * res[i].hstride;
@@ -296,11 +296,180 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
             }
             if (probs.empty()) continue;
             hipError_t e = dt == SALUS_BF16
-                               ? launch_grouped_bf16(probs.data(), (uint32_t)probs.size(), (hipStream_t)stream, &pool->gemm_launches)
+                               ? launch_grouped_bf16(probs.data(), (uint32_t)probs.size(), false, (hipStream_t)stream, &pool->gemm_launches)
                                : launch_grouped_f32(probs.data(), (uint32_t)probs.size(), (hipStream_t)stream, &pool->gemm_launches);
             if (e != hipSuccess) return set_error(pool, SALUS_EHIP, hipGetErrorString(e));
         }
     }
+    return SALUS_OK;
+}
+
+static uint64_t up256(uint64_t v) { return (v + 255) & ~(uint64_t)255; }
+
+// Scratch layout of a training step inside the lane: H_1 .. H_{L-1} (bf16, kept
+// for the backward pass), then two gradient buffers of M x max_l(N_l) bf16.
+uint64_t salus_train_work_bytes(uint32_t M, const salus_train_layer *layers, uint32_t n_layers)
+{
+    if (!layers || n_layers == 0) return 0;
+    uint64_t total = 0, max_n = 0;
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        if (l + 1 < n_layers) total += up256((uint64_t)M * layers[l].N * 2);
+        max_n = std::max<uint64_t>(max_n, layers[l].N);
+    }
+    return total + 2 * up256((uint64_t)M * max_n * 2);
+}
+
+int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *descs, uint32_t n,
+                                 void *stream_)
+{
+    CHECK_POOL(pool);
+    if (n == 0) return SALUS_OK;
+    if (!descs) return set_error(pool, SALUS_EINVAL, "null descriptor array");
+    if (!pool->ops.present()) return set_error(pool, SALUS_EINVAL, "pool has no device memory");
+    hipStream_t stream = (hipStream_t)stream_;
+    char *base = pool->ops.base;
+    struct Resolved {
+        char *persist, *lane;
+        std::vector<uint64_t> h_off;   // lane offset of H_l, l = 0 (= x) .. L-1
+        uint64_t g_off[2];
+    };
+    std::vector<Resolved> res(n);
+    std::vector<int32_t> lanes_used;
+    uint32_t depth = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        const salus_train_desc &d = descs[i];
+        const Job *j = pool->core->job(d.job);
+        if (!j) return set_error(pool, SALUS_EINVAL, "descriptor names an unknown job");
+        if (j->state != SALUS_JOB_RESIDENT)
+            return set_error(pool, SALUS_ENOTRESIDENT, "job " + std::to_string(d.job) + " is not resident");
+        if (std::find(lanes_used.begin(), lanes_used.end(), j->lane) != lanes_used.end())
+            return set_error(pool, SALUS_EBUSY, "two jobs of lane " + std::to_string(j->lane) +
+                                                    " in one packed iteration");
+        lanes_used.push_back(j->lane);
+        if (d.n_layers == 0 || !d.layers || d.M == 0) return set_error(pool, SALUS_EINVAL, "empty job descriptor");
+        uint64_t lane_size = 0;
+        const uint64_t lane_off = pool->core->lane_base(j->lane, &lane_size);
+        for (uint32_t l = 0; l < d.n_layers; ++l) {
+            const salus_train_layer &L = d.layers[l];
+            if (L.K == 0 || L.N == 0 || L.K % 8 || L.N % 8)
+                return set_error(pool, SALUS_EINVAL, "K and N must be positive multiples of 8");
+            if (l && L.K != d.layers[l - 1].N) return set_error(pool, SALUS_EINVAL, "layer widths do not chain");
+            const uint64_t elems = (uint64_t)L.K * L.N;
+            if (L.wb_off % 16 || L.wb_off > j->P || elems * 2 > j->P - L.wb_off || L.wm_off % 16 ||
+                L.wm_off > j->P || elems * 4 > j->P - L.wm_off)
+                return set_error(pool, SALUS_EINVAL, "weights outside the persistent block");
+            if (overlap(L.wb_off, elems * 2, L.wm_off, elems * 4))
+                return set_error(pool, SALUS_EINVAL, "working and master weights overlap");
+        }
+        const uint32_t n_last = d.layers[d.n_layers - 1].N;
+        struct Range { uint64_t off, len; };
+        const Range r[5] = {{d.x_off, (uint64_t)d.M * d.layers[0].K * 2},
+                            {d.labels_off, (uint64_t)d.M * 4},
+                            {d.logits_off, (uint64_t)d.M * n_last * 4},
+                            {d.loss_off, 4},
+                            {d.work_off, salus_train_work_bytes(d.M, d.layers, d.n_layers)}};
+        for (int a = 0; a < 5; ++a) {
+            if (r[a].off % 16 || r[a].off > lane_size || r[a].len > lane_size - r[a].off)
+                return set_error(pool, SALUS_EINVAL, "buffer outside the job's lane");
+            for (int b = 0; b < a; ++b)
+                if (overlap(r[a].off, r[a].len, r[b].off, r[b].len))
+                    return set_error(pool, SALUS_EINVAL, "lane buffers overlap");
+        }
+        Resolved &R = res[i];
+        R.persist = base + j->off;
+        R.lane = base + lane_off;
+        R.h_off.push_back(d.x_off);
+        uint64_t at = d.work_off, max_n = 0;
+        for (uint32_t l = 0; l < d.n_layers; ++l) {
+            if (l + 1 < d.n_layers) {
+                R.h_off.push_back(at);
+                at += up256((uint64_t)d.M * d.layers[l].N * 2);
+            }
+            max_n = std::max<uint64_t>(max_n, d.layers[l].N);
+        }
+        R.g_off[0] = at;
+        R.g_off[1] = at + up256((uint64_t)d.M * max_n * 2);
+        depth = std::max(depth, d.n_layers);
+    }
+    hipError_t e = hipSuccess;
+    uint64_t *count = &pool->gemm_launches;
+    // forward, one launch per layer depth
+    std::vector<Problem> probs;
+    for (uint32_t l = 0; l < depth && e == hipSuccess; ++l) {
+        probs.clear();
+        for (uint32_t i = 0; i < n; ++i) {
+            const salus_train_desc &d = descs[i];
+            if (l >= d.n_layers) continue;
+            const bool last = l + 1 == d.n_layers;
+            Problem pr{};
+            pr.W = res[i].persist + d.layers[l].wb_off;
+            pr.X = res[i].lane + res[i].h_off[l];
+            pr.Y = last ? res[i].lane + d.logits_off : res[i].lane + res[i].h_off[l + 1];
+            pr.M = d.M;
+            pr.K = d.layers[l].K;
+            pr.N = d.layers[l].N;
+            pr.flags = last ? (uint32_t)SALUS_ACT_NONE : ((uint32_t)SALUS_ACT_RELU | kOutBf16);
+            probs.push_back(pr);
+        }
+        e = launch_grouped_bf16(probs.data(), (uint32_t)probs.size(), false, stream, count);
+    }
+    // loss and its gradient
+    if (e == hipSuccess) {
+        std::vector<LossProblem> lp;
+        for (uint32_t i = 0; i < n; ++i) {
+            const salus_train_desc &d = descs[i];
+            LossProblem p{};
+            p.logits = (const float *)(res[i].lane + d.logits_off);
+            p.labels = (const int32_t *)(res[i].lane + d.labels_off);
+            p.grad = res[i].lane + res[i].g_off[0];
+            p.loss = (float *)(res[i].lane + d.loss_off);
+            p.M = d.M;
+            p.N = d.layers[d.n_layers - 1].N;
+            lp.push_back(p);
+        }
+        e = launch_softmax_xent(lp.data(), (uint32_t)lp.size(), stream, count);
+    }
+    // backward: layer `back` counted from each job's last layer, so that jobs of
+    // different depth still share launches; input gradient first (it reads the
+    // weights the update is about to overwrite)
+    std::vector<UpdateProblem> ups;
+    for (uint32_t back = 0; back < depth && e == hipSuccess; ++back) {
+        probs.clear();
+        ups.clear();
+        for (uint32_t i = 0; i < n; ++i) {
+            const salus_train_desc &d = descs[i];
+            if (back >= d.n_layers) continue;
+            const uint32_t l = d.n_layers - 1 - back;
+            const salus_train_layer &L = d.layers[l];
+            char *g_cur = res[i].lane + res[i].g_off[back & 1];
+            char *g_next = res[i].lane + res[i].g_off[(back + 1) & 1];
+            if (l > 0) {
+                Problem pr{};
+                pr.W = res[i].persist + L.wb_off;      // K x N: rows are the output columns of dX
+                pr.X = g_cur;
+                pr.Y = g_next;
+                pr.aux = res[i].lane + res[i].h_off[l];
+                pr.M = d.M;
+                pr.K = L.N;
+                pr.N = L.K;
+                pr.flags = kOutBf16 | kMaskPositive;
+                probs.push_back(pr);
+            }
+            UpdateProblem up{};
+            up.H = res[i].lane + res[i].h_off[l];
+            up.G = g_cur;
+            up.Wm = (float *)(res[i].persist + L.wm_off);
+            up.Wb = res[i].persist + L.wb_off;
+            up.M = d.M;
+            up.K = L.K;
+            up.N = L.N;
+            up.lr = d.lr;
+            ups.push_back(up);
+        }
+        if (!probs.empty()) e = launch_grouped_bf16(probs.data(), (uint32_t)probs.size(), true, stream, count);
+        if (e == hipSuccess) e = launch_grouped_dw_sgd(ups.data(), (uint32_t)ups.size(), stream, count);
+    }
+    if (e != hipSuccess) return set_error(pool, SALUS_EHIP, hipGetErrorString(e));
     return SALUS_OK;
 }
 

@@ -32,17 +32,41 @@ hipError_t launch_check_pattern(const void *dev, uint64_t nbytes, uint64_t seed,
 
 // ---- grouped GEMM -----------------------------------------------------------
 struct Problem {
-    const void *W;       // K x N row-major
+    const void *W;       // K x N row-major; with kTransW: N x K row-major (Y = X . W^T)
     const void *X;       // M x K row-major
     void *Y;             // M x N row-major
+    const void *aux;     // kMaskPositive: M x N bf16, Y is zeroed where aux <= 0
     uint32_t M, K, N;
-    uint32_t flags;      // bits 0-7 activation, bit 8: store Y as bf16
+    uint32_t flags;      // bits 0-7 activation, then the bits below
 };
 constexpr uint32_t kMaxProblems = 64;       // problems per launch (one per wavefront lane)
-constexpr uint32_t kOutBf16 = 1u << 8;
+constexpr uint32_t kOutBf16 = 1u << 8;      // store Y as bf16 (round to nearest even)
+constexpr uint32_t kMaskPositive = 1u << 9; // multiply Y by [aux > 0] (ReLU derivative)
 
 // One launch (or several when n > kMaxProblems): Y_g = act(X_g . W_g) for all g.
-hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches);
+hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipStream_t stream,
+                               uint64_t *launches);
 hipError_t launch_grouped_f32(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches);
+
+// ---- training step ------------------------------------------------------------
+struct LossProblem {
+    const float *logits;     // M x N
+    const int32_t *labels;   // M
+    void *grad;              // M x N bf16: (softmax - onehot) / M
+    float *loss;             // mean cross-entropy
+    uint32_t M, N;
+};
+struct UpdateProblem {
+    const void *H;           // M x K bf16 (layer input)
+    const void *G;           // M x N bf16 (gradient of the layer output)
+    float *Wm;               // K x N float master weights, updated in place
+    void *Wb;                // K x N bf16 working copy, rewritten
+    uint32_t M, K, N;
+    float lr;
+};
+hipError_t launch_softmax_xent(const LossProblem *p, uint32_t n, hipStream_t stream, uint64_t *launches);
+// Wm <- Wm - lr * (H^T . G), Wb <- bf16(Wm), all problems in one launch.
+hipError_t launch_grouped_dw_sgd(const UpdateProblem *p, uint32_t n, hipStream_t stream,
+                                 uint64_t *launches);
 
 }  // namespace salus

@@ -132,8 +132,10 @@ constexpr int reduce_lds_floats() { return kWaves * 3 * (NACC < 16 ? NACC : 16) 
 // MFMA i, whose 16 output columns are n0 + 8c + i.  The A operand is
 // X[m0 + c][k0+8g .. +7].  Both operands use the same 8 k-values per lane
 // group, which is all the MFMA contraction needs.
+// TW (backward pass, dX = dY . W^T): W is stored N x K, so the eight k-values of
+// output column n0+8c+i are contiguous in row n0+8c+i and are loaded as they are.
 // ---------------------------------------------------------------------------
-template <int MT>
+template <int MT, bool TW>
 __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
 {
     constexpr int TM = 16 * MT, TN = 128, NACC = MT * 8;
@@ -159,10 +161,10 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
         const uint32_t kb = 32u * (uint32_t)s + 8u * (uint32_t)g;
         const bool k_ok = s < nsteps && kb < K;
 #pragma unroll
-        for (int r = 0; r < 8; ++r)
-            w[r] = (k_ok && col_ok)
-                       ? __builtin_nontemporal_load((const u32x4 *)(W + (size_t)(kb + r) * N + ncol))
-                       : zero;
+        for (int r = 0; r < 8; ++r) {
+            const uint16_t *at = TW ? W + (size_t)(ncol + r) * K + kb : W + (size_t)(kb + r) * N + ncol;
+            w[r] = (k_ok && col_ok) ? __builtin_nontemporal_load((const u32x4 *)at) : zero;
+        }
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             const uint32_t row = tile.m0 + 16 * t + c;
@@ -174,10 +176,14 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
         for (int i = 0; i < 8; ++i) {
             // column i of the 8x8 block: dword j = (row 2j, row 2j+1)
             u32x4 b;
+            if (TW) {
+                b = w[i];
+            } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                b[j] = __builtin_amdgcn_perm(w[2 * j + 1][i >> 1], w[2 * j][i >> 1],
-                                             (i & 1) ? 0x07060302u : 0x05040100u);
+                for (int j = 0; j < 4; ++j)
+                    b[j] = __builtin_amdgcn_perm(w[2 * j + 1][i >> 1], w[2 * j][i >> 1],
+                                                 (i & 1) ? 0x07060302u : 0x05040100u);
+            }
 #pragma unroll
             for (int t = 0; t < MT; ++t)
                 acc[t * 8 + i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
@@ -209,6 +215,15 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
         float v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = activate(own[t * 8 + i], act);
+        if (p.flags & kMaskPositive) {
+            // ReLU derivative taken from the stored bf16 activation (sign bit clear, not zero)
+            const u32x4 h = *(const u32x4 *)((const uint16_t *)p.aux + (size_t)row * N + ncol);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t bits = (h[i >> 1] >> ((i & 1) * 16)) & 0xffffu;
+                if ((bits & 0x8000u) || !(bits & 0x7fffu)) v[i] = 0.0f;
+            }
+        }
         if (p.flags & kOutBf16) {
             u32x4 o;
 #pragma unroll
@@ -328,15 +343,20 @@ static hipError_t launch_groups(const Problem *p, uint32_t n, uint32_t tn, uint3
     return hipSuccess;
 }
 
-hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches)
+hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipStream_t stream,
+                               uint64_t *launches)
 {
     auto launch = [&](int mt, const GroupArgs &a, uint32_t tiles) {
-        if (mt == 1)
-            hipLaunchKernelGGL(grouped_dense_bf16<1>, dim3(tiles), dim3(kGemmThreads), 0, stream, a);
-        else if (mt == 2)
-            hipLaunchKernelGGL(grouped_dense_bf16<2>, dim3(tiles), dim3(kGemmThreads), 0, stream, a);
-        else
-            hipLaunchKernelGGL(grouped_dense_bf16<4>, dim3(tiles), dim3(kGemmThreads), 0, stream, a);
+        const dim3 grid(tiles), block(kGemmThreads);
+        if (trans_w) {
+            if (mt == 1) hipLaunchKernelGGL((grouped_dense_bf16<1, true>), grid, block, 0, stream, a);
+            else if (mt == 2) hipLaunchKernelGGL((grouped_dense_bf16<2, true>), grid, block, 0, stream, a);
+            else hipLaunchKernelGGL((grouped_dense_bf16<4, true>), grid, block, 0, stream, a);
+        } else {
+            if (mt == 1) hipLaunchKernelGGL((grouped_dense_bf16<1, false>), grid, block, 0, stream, a);
+            else if (mt == 2) hipLaunchKernelGGL((grouped_dense_bf16<2, false>), grid, block, 0, stream, a);
+            else hipLaunchKernelGGL((grouped_dense_bf16<4, false>), grid, block, 0, stream, a);
+        }
     };
     return launch_groups(p, n, 128, 16, 32, launch, launches);
 }

@@ -52,6 +52,17 @@ class GemmDesc(C.Structure):
                 ("x_off", C.c_uint64), ("y_off", C.c_uint64), ("h_off", C.c_uint64)]
 
 
+class TrainLayer(C.Structure):
+    _fields_ = [("K", C.c_uint32), ("N", C.c_uint32), ("wb_off", C.c_uint64), ("wm_off", C.c_uint64)]
+
+
+class TrainDesc(C.Structure):
+    _fields_ = [("job", C.c_int32), ("M", C.c_uint32), ("n_layers", C.c_uint32), ("lr", C.c_float),
+                ("layers", C.POINTER(TrainLayer)),
+                ("x_off", C.c_uint64), ("labels_off", C.c_uint64), ("logits_off", C.c_uint64),
+                ("loss_off", C.c_uint64), ("work_off", C.c_uint64)]
+
+
 class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
         "rounds", "iterations", "bytes_d2h", "bytes_h2d", "bytes_d2d", "moves", "compactions",
@@ -76,6 +87,8 @@ _PROTOS = {
     "salus_job_read": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
     "salus_schedule_iteration": [C.c_void_p, C.POINTER(Slot), C.c_uint32, C.POINTER(C.c_uint32)],
     "salus_grouped_forward": [C.c_void_p, C.POINTER(GemmDesc), C.c_uint32, C.c_void_p],
+    "salus_train_work_bytes": [C.c_uint32, C.POINTER(TrainLayer), C.c_uint32],
+    "salus_grouped_train_step": [C.c_void_p, C.POINTER(TrainDesc), C.c_uint32, C.c_void_p],
     "salus_switch_out": [C.c_void_p, C.c_int32, C.c_void_p],
     "salus_switch_in": [C.c_void_p, C.c_int32],
     "salus_compact": [C.c_void_p, C.POINTER(Move), C.c_uint32, C.POINTER(C.c_uint32)],
@@ -106,7 +119,8 @@ def lib():
         for name, args in _PROTOS.items():
             fn = getattr(L, name)
             fn.argtypes = args
-            fn.restype = C.c_char_p if name == "salus_last_error" else C.c_int32
+            fn.restype = (C.c_char_p if name == "salus_last_error" else
+                          C.c_uint64 if name == "salus_train_work_bytes" else C.c_int32)
         _lib = L
     return _lib
 
@@ -222,6 +236,26 @@ class Pool:
         return self._check(self._lib.salus_grouped_forward(self._h, descs, n, stream),
                            (OK, EINVAL, ENOTRESIDENT, EBUSY))
 
+    @staticmethod
+    def make_train_descs(items):
+        """items: dicts(job, M, lr, layers=[(K, N, wb_off, wm_off)], x_off, labels_off,
+        logits_off, loss_off, work_off)."""
+        items = list(items)
+        arr = (TrainDesc * len(items))()
+        keep = []
+        for i, it in enumerate(items):
+            L = (TrainLayer * len(it["layers"]))(*[TrainLayer(*t) for t in it["layers"]])
+            keep.append(L)
+            arr[i] = TrainDesc(it["job"], it["M"], len(it["layers"]), it["lr"], L, it["x_off"],
+                               it["labels_off"], it["logits_off"], it["loss_off"], it["work_off"])
+        return arr, keep
+
+    def grouped_train_step(self, descs, n=None, stream=None):
+        if n is None:
+            n = len(descs)
+        return self._check(self._lib.salus_grouped_train_step(self._h, descs, n, stream),
+                           (OK, EINVAL, ENOTRESIDENT, EBUSY))
+
     # -- switching -----------------------------------------------------------------
     def switch_out(self, job, pinned_ptr=None):
         return self._lib.salus_switch_out(self._h, job, pinned_ptr)
@@ -246,6 +280,12 @@ class Pool:
         n = C.c_uint32()
         self._lib.salus_poll_events(self._h, ev, cap, C.byref(n))
         return [(ev[i].kind, ev[i].a, ev[i].b) for i in range(n.value)]
+
+
+def train_work_bytes(M, layers):
+    """layers: [(K, N, wb_off, wm_off)]"""
+    L = (TrainLayer * len(layers))(*[TrainLayer(*t) for t in layers])
+    return lib().salus_train_work_bytes(M, L, len(layers))
 
 
 def scan_u64(values, scratch_ptr, stream=None):

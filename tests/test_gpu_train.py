@@ -1,0 +1,195 @@
+"""GPU parity of the packed training step (forward + loss + backward + SGD)
+against the oracle's step, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import train
+from paper_1902_04610_amd import salus, synth
+from gpu_util import DevicePool, norm_rel_err
+
+pytestmark = pytest.mark.gpu
+
+# Tolerances.  Forward products are exact in float (bf16 x bf16), sums in float
+# against the oracle's double: logits within 2e-3 of their largest magnitude
+# (2e-2 is the stated bound).  The weight gradient sums only M terms; its inputs
+# differ from the oracle's by rare 1-ulp bf16 flips of an activation or of the
+# incoming gradient: within 5e-3 of the largest gradient entry.  Master weights
+# then differ by at most lr times that, plus one float rounding.
+# In a deep stack one flipped activation (2^-8 of its value) shifts the whole
+# next row by ~1e-4 of its scale, which flips a few percent of that row in turn:
+# the error of a 4-layer net's logits reaches a few 1e-3 on such rows, so the
+# derived bound is 1e-2 per output matrix (half the stated 2e-2).
+TOL_LOGITS, TOL_LOGITS_STATED, TOL_GRAD = 1e-2, 2e-2, 5e-3
+
+
+def up(v):
+    return (v + 255) // 256 * 256
+
+
+class TrainJob:
+    def __init__(self, dp, dims, M, lr, Wm):
+        self.dims, self.M, self.lr = dims, M, np.float32(lr)
+        self.layers, off = [], 0
+        for K, N in zip(dims[:-1], dims[1:]):
+            wb, wm = off, off + up(K * N * 2)
+            off = wm + up(K * N * 4)
+            self.layers.append((K, N, wb, wm))
+        self.P = off
+        self.x_off = 0
+        self.labels_off = up(M * dims[0] * 2)
+        self.logits_off = self.labels_off + up(M * 4)
+        self.loss_off = self.logits_off + up(M * dims[-1] * 4)
+        self.work_off = self.loss_off + 256
+        work = salus.train_work_bytes(M, self.layers)
+        assert work == sum(up(M * n * 2) for n in dims[1:-1]) + 2 * up(M * max(dims[1:]) * 2)
+        self.E = self.work_off + work
+        st, self.job = dp.pool.lane_alloc(self.P, self.E, 0, 10 ** 6)
+        assert st == salus.OK
+        self.dp = dp
+        self.Wm = [w.copy() for w in Wm]                       # oracle's copies
+        self.Wb = [synth.f32_to_bf16_bits(w) for w in Wm]
+        q = dp.pool.job_query(self.job)
+        for (K, N, wb, wm), m, b in zip(self.layers, self.Wm, self.Wb):
+            dp.write(q.persist_off + wb, b)
+            dp.write(q.persist_off + wm, m)
+
+    def desc(self):
+        return dict(job=self.job, M=self.M, lr=float(self.lr), layers=self.layers, x_off=self.x_off,
+                    labels_off=self.labels_off, logits_off=self.logits_off, loss_off=self.loss_off,
+                    work_off=self.work_off)
+
+    def put_batch(self, Xb, labels):
+        q = self.dp.pool.job_query(self.job)
+        self.dp.write(q.lane_off + self.x_off, Xb)
+        self.dp.write(q.lane_off + self.labels_off, labels)
+
+    def gpu_state(self):
+        q = self.dp.pool.job_query(self.job)
+        Wm = [self.dp.read(q.persist_off + wm, K * N * 4, np.float32).reshape(K, N).copy()
+              for K, N, wb, wm in self.layers]
+        Wb = [self.dp.read(q.persist_off + wb, K * N * 2, np.uint16).reshape(K, N).copy()
+              for K, N, wb, wm in self.layers]
+        logits = self.dp.read(q.lane_off + self.logits_off, self.M * self.dims[-1] * 4,
+                              np.float32).reshape(self.M, self.dims[-1]).copy()
+        loss = float(self.dp.read(q.lane_off + self.loss_off, 4, np.float32)[0])
+        return Wm, Wb, logits, loss
+
+
+def check_step(job, Xb, labels, step):
+    before = [w.copy() for w in job.Wm]
+    loss, logits, grads = train.train_step(Xb, labels, job.Wm, job.Wb, job.lr)    # oracle, in place
+    gWm, gWb, glogits, gloss = job.gpu_state()
+    tag = (job.job, step)
+    e = norm_rel_err(glogits, logits)
+    assert e < TOL_LOGITS and e < TOL_LOGITS_STATED, (tag, e)
+    assert abs(gloss - loss) < 2e-3 * max(1.0, abs(loss)), (tag, gloss, loss)
+    for l, (g, wm_gpu, wm_ref, wb_gpu, wb_ref, w0) in enumerate(zip(grads, gWm, job.Wm, gWb, job.Wb, before)):
+        gmax = np.abs(g).max()
+        if job.lr > 0:
+            g_gpu = (w0.astype(np.float64) - wm_gpu.astype(np.float64)) / float(job.lr)
+            # recovering the gradient from the update is limited by the float spacing of W
+            slack = np.spacing(np.abs(w0).max()) / float(job.lr)
+            assert np.abs(g_gpu - g).max() < TOL_GRAD * gmax + 2 * slack, (tag, l)
+        bound = float(job.lr) * TOL_GRAD * gmax + np.spacing(np.abs(wm_ref).max())
+        assert np.abs(wm_gpu - wm_ref).max() <= bound, (tag, l, np.abs(wm_gpu - wm_ref).max(), bound)
+        assert np.array_equal(wb_gpu, synth.f32_to_bf16_bits(wm_gpu)), (tag, l)   # working copy = bf16(master)
+        diff = wb_gpu != wb_ref
+        assert diff.mean() < 2e-3, (tag, l, diff.mean())                           # rare 1-ulp flips only
+        assert np.abs(synth.bf16_bits_to_f32(wb_gpu) - synth.bf16_bits_to_f32(wb_ref)).max() <= \
+            2.0 ** -7 * np.abs(wm_ref).max()
+    # continue from the GPU's weights so that errors do not compound across steps
+    job.Wm, job.Wb = gWm, gWb
+
+
+def run(configs, steps, seed):
+    rng = np.random.default_rng(seed)
+    cap = 0
+    specs = []
+    for dims, M, lr in configs:
+        Wm = [(rng.standard_normal((K, N)) / np.sqrt(K)).astype(np.float32)
+              for K, N in zip(dims[:-1], dims[1:])]
+        specs.append((dims, M, lr, Wm))
+        cap += sum(up(K * N * 2) + up(K * N * 4) for K, N in zip(dims[:-1], dims[1:]))
+        cap += up(M * dims[0] * 2) + up(M * 4) + up(M * dims[-1] * 4) + 256 + \
+            sum(up(M * n * 2) for n in dims[1:-1]) + 2 * up(M * max(dims[1:]) * 2) + 4096
+    dp = DevicePool(up(cap), policy=salus.POLICY_PACK)
+    jobs = [TrainJob(dp, *s) for s in specs]
+    descs, keep = salus.Pool.make_train_descs(j.desc() for j in jobs)
+    for step in range(steps):
+        sched = dp.pool.schedule_iteration()
+        assert [j for j, _ in sched] == [j.job for j in jobs]
+        batches = []
+        for j in jobs:
+            Xb = synth.f32_to_bf16_bits(rng.standard_normal((j.M, j.dims[0])).astype(np.float32))
+            labels = rng.integers(0, j.dims[-1], j.M).astype(np.int32)
+            j.put_batch(Xb, labels)
+            batches.append((Xb, labels))
+        before = dp.pool.stats()["gemm_launches"]
+        assert dp.pool.grouped_train_step(descs, stream=dp.stream) == salus.OK
+        dp.sync()
+        depth = max(len(j.layers) for j in jobs)
+        # forward + loss + (input gradient, update) per layer, shared by all jobs
+        assert dp.pool.stats()["gemm_launches"] - before == depth + 1 + (depth - 1) + depth
+        for j, (Xb, labels) in zip(jobs, batches):
+            check_step(j, Xb, labels, step)
+    dp.close()
+
+
+def test_train_step_ragged_shapes():
+    run([((72, 136, 264, 40), 13, 0.05), ((264, 72, 8), 64, 0.01), ((40, 520, 136), 33, 0.1),
+         ((128, 128), 1, 0.02)], steps=2, seed=0)
+
+
+def test_train_step_lr_zero_changes_nothing():
+    dims, M = (136, 264, 72), 20
+    rng = np.random.default_rng(5)
+    Wm = [(rng.standard_normal((K, N)) / np.sqrt(K)).astype(np.float32) for K, N in zip(dims[:-1], dims[1:])]
+    dp = DevicePool(1 << 22, policy=salus.POLICY_PACK)
+    j = TrainJob(dp, dims, M, 0.0, Wm)
+    j.put_batch(synth.f32_to_bf16_bits(rng.standard_normal((M, dims[0])).astype(np.float32)),
+                rng.integers(0, dims[-1], M).astype(np.int32))
+    descs, keep = salus.Pool.make_train_descs([j.desc()])
+    assert dp.pool.grouped_train_step(descs, stream=dp.stream) == salus.OK
+    gWm, gWb, _, _ = j.gpu_state()
+    for a, b in zip(gWm, Wm):
+        assert np.array_equal(a, b)                    # bit-identical master weights
+    for a, b in zip(gWb, j.Wb):
+        assert np.array_equal(a, b)
+    dp.close()
+
+
+def test_workload3_hyperparameter_tuning_scaled():
+    """Eight jobs of one architecture with different learning rates (widths / 8)."""
+    w = synth.workload3(seed=2, jobs=8, dims=(256, 256, 256, 256, 128), batch=64, steps=3)
+    cap = 8 * (4 * up(256 * 256 * 6) + (1 << 20))
+    dp = DevicePool(cap, policy=salus.POLICY_PACK)
+    jobs = [TrainJob(dp, w["dims"], w["batch"], w["lr"][k], w["Wm"][k]) for k in range(8)]
+    assert len(dp.pool.lanes()) == 8
+    descs, keep = salus.Pool.make_train_descs(j.desc() for j in jobs)
+    for step in range(w["steps"]):
+        assert len(dp.pool.schedule_iteration()) == 8          # PACK: every lane runs
+        for k, j in enumerate(jobs):
+            j.put_batch(w["X"][k][step], w["labels"][k][step])
+        assert dp.pool.grouped_train_step(descs, stream=dp.stream) == salus.OK
+        dp.sync()
+        for k, j in enumerate(jobs):
+            check_step(j, w["X"][k][step], w["labels"][k][step], step)
+    dp.close()
+
+
+def test_train_step_rejects_bad_descriptors():
+    dims, M = (64, 64, 16), 8
+    rng = np.random.default_rng(1)
+    Wm = [rng.standard_normal((K, N)).astype(np.float32) for K, N in zip(dims[:-1], dims[1:])]
+    dp = DevicePool(1 << 21, policy=salus.POLICY_PACK)
+    j = TrainJob(dp, dims, M, 0.1, Wm)
+    d = j.desc()
+    mk = lambda **kw: salus.Pool.make_train_descs([dict(d, **kw)])[0]
+    assert dp.pool.grouped_train_step(mk(layers=[(64, 60, 0, 16384)])) == salus.EINVAL     # N % 8
+    assert dp.pool.grouped_train_step(mk(layers=[(64, 64, 0, 4096)])) == salus.EINVAL      # copies overlap
+    assert dp.pool.grouped_train_step(mk(work_off=j.E - 256)) == salus.EINVAL               # scratch outside lane
+    assert dp.pool.grouped_train_step(mk(labels_off=0)) == salus.EINVAL                     # overlaps x
+    assert dp.pool.switch_out(j.job) == salus.OK
+    assert dp.pool.grouped_train_step(mk()) == salus.ENOTRESIDENT
+    dp.close()
