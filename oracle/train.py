@@ -23,6 +23,12 @@ definition written out with the primitives of dense.c:
 Reading: the ReLU derivative is taken from the stored bf16 activation
 (H > 0), which is what a backward pass has at hand.
 
+The step is split into its two passes so that a test can hand the backward
+pass the activations and logits another implementation produced: whether a
+unit's derivative is 0 or 1 is decided by the sign of a stored activation, and
+two forward passes that differ by one rounding can disagree on units that sit
+within that rounding of zero.
+
 Pins: tests/test_oracle_train.py (torch double autograd as a second opinion,
 finite differences at a point where no rounding occurs, lr = 0).
 """
@@ -31,11 +37,9 @@ import numpy as np
 from . import dense
 
 
-def train_step(Xb, labels, Wm, Wb, lr):
-    """Xb: (M, K0) bf16 bits; labels: (M,) int32; Wm: list of float32 (K, N)
-    arrays, Wb: list of uint16 (K, N) arrays - both updated IN PLACE.
-    Returns (loss, logits, grads) where grads are the float dW of every layer."""
-    L = len(Wm)
+def forward(Xb, Wb):
+    """Returns (H, logits): H = [H_0 = X, H_1, ..., H_{L-1}] as bf16 bits."""
+    L = len(Wb)
     H = [np.ascontiguousarray(Xb, np.uint16)]
     Z = None
     for l in range(L):
@@ -43,15 +47,31 @@ def train_step(Xb, labels, Wm, Wb, lr):
         Z = dense.dense_bf16(H[l], Wb[l], act)          # relu already applied for hidden layers
         if l + 1 < L:
             H.append(dense.round_bf16(Z))
-    logits = Z
+    return H, Z
+
+
+def backward_update(H, logits, labels, Wm, Wb, lr):
+    """Loss, gradients and the SGD update.  Wm (float32) and Wb (uint16) are
+    updated IN PLACE.  Returns (loss, grads, G) with grads[l] the float dW_l and
+    G[l] the bf16 gradient that entered layer l's backward products."""
+    L = len(Wm)
     loss, dZ = dense.softmax_xent(logits, labels)
-    grads = [None] * L
+    grads, G = [None] * L, [None] * L
     for l in range(L - 1, -1, -1):
-        G = dense.round_bf16(dZ)
-        grads[l] = dense.dense_bwd_weight_bf16(H[l], G)
+        G[l] = dense.round_bf16(dZ)
+        grads[l] = dense.dense_bwd_weight_bf16(H[l], G[l])
         if l > 0:
-            dH = dense.dense_bwd_input_bf16(G, Wb[l])
+            dH = dense.dense_bwd_input_bf16(G[l], Wb[l])
             positive = dense.bf16_to_f32(H[l]) > 0
             dZ = np.where(positive, dH, np.float32(0)).astype(np.float32)
         dense.sgd_update(Wm[l], Wb[l], grads[l], lr)
+    return loss, grads, G
+
+
+def train_step(Xb, labels, Wm, Wb, lr):
+    """Xb: (M, K0) bf16 bits; labels: (M,) int32; Wm: list of float32 (K, N)
+    arrays, Wb: list of uint16 (K, N) arrays - both updated IN PLACE.
+    Returns (loss, logits, grads) where grads are the float dW of every layer."""
+    H, logits = forward(Xb, Wb)
+    loss, grads, _ = backward_update(H, logits, labels, Wm, Wb, lr)
     return loss, logits, grads

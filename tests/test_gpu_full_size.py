@@ -218,3 +218,35 @@ def test_forced_compaction_200GB():
     assert dp.pool.compact() == []
     print("forced compaction: moves", len(plan), "GB moved", sum(m[2] for m in plan) / 1e9)
     dp.close()
+
+
+# --------------------------------------------------------------------------- workload 3
+def test_workload3_full_size_sampled_job():
+    """Eight 2048-wide 4-layer training jobs in one packed step; the oracle
+    recomputes the whole step of two sampled jobs."""
+    from oracle import train
+    from test_gpu_train import TrainJob, check_step_stagewise, up
+    dims, M, JOBS = (2048, 2048, 2048, 2048, 1000), 64, 8
+    rng = np.random.Generator(np.random.PCG64(2))
+    per_job = sum(up(k * n * 6) + 512 for k, n in zip(dims[:-1], dims[1:]))
+    dp = big_pool(up(JOBS * (per_job + 8 * MiB)), policy=salus.POLICY_PACK)
+    lrs = (10.0 ** rng.uniform(-4, -1, JOBS)).astype(np.float32)
+    jobs, batches = [], []
+    for k in range(JOBS):
+        Wm = [(rng.standard_normal((K, N), dtype=np.float32) * np.float32(1 / np.sqrt(K)))
+              for K, N in zip(dims[:-1], dims[1:])]
+        jobs.append(TrainJob(dp, dims, M, lrs[k], Wm))
+        if k not in (1, 6):
+            jobs[-1].Wm = jobs[-1].Wb = None          # only the sampled jobs keep host copies
+        Xb = synth.f32_to_bf16_bits(rng.standard_normal((M, dims[0]), dtype=np.float32))
+        labels = rng.integers(0, dims[-1], M).astype(np.int32)
+        jobs[-1].put_batch(Xb, labels)
+        batches.append((Xb, labels))
+    assert len(dp.pool.schedule_iteration()) == JOBS
+    descs, keep = salus.Pool.make_train_descs(j.desc() for j in jobs)
+    assert dp.pool.grouped_train_step(descs, stream=dp.stream) == salus.OK
+    dp.sync()
+    assert dp.pool.stats()["gemm_launches"] == 4 + 1 + 3 + 4
+    for k in (1, 6):
+        check_step_stagewise(jobs[k], *batches[k])
+    dp.close()

@@ -20,7 +20,12 @@ pytestmark = pytest.mark.gpu
 # next row by ~1e-4 of its scale, which flips a few percent of that row in turn:
 # the error of a 4-layer net's logits reaches a few 1e-3 on such rows, so the
 # derived bound is 1e-2 per output matrix (half the stated 2e-2).
-TOL_LOGITS, TOL_LOGITS_STATED, TOL_GRAD = 1e-2, 2e-2, 5e-3
+# A hidden activation that lands within that noise of zero changes the ReLU
+# derivative outright; the weight gradient of that unit then differs by one
+# whole term of the M-term batch sum.  In small nets this does not occur (the
+# derived bound holds); at width 2048 it does on a handful of columns, so the
+# full-size test uses the stated bound for the gradient (TOL_GRAD_STATED).
+TOL_LOGITS, TOL_LOGITS_STATED, TOL_GRAD, TOL_GRAD_STATED = 1e-2, 2e-2, 5e-3, 2e-2
 
 
 def up(v):
@@ -76,7 +81,46 @@ class TrainJob:
         return Wm, Wb, logits, loss
 
 
-def check_step(job, Xb, labels, step):
+def gpu_hidden(job):
+    """The hidden activations H_1 .. H_{L-1} (bf16 bits) the GPU kept for its backward pass."""
+    q = job.dp.pool.job_query(job.job)
+    out, at = [], q.lane_off + job.work_off
+    for n in job.dims[1:-1]:
+        out.append(job.dp.read(at, job.M * n * 2, np.uint16).reshape(job.M, n).copy())
+        at += up(job.M * n * 2)
+    return out
+
+
+def check_step_stagewise(job, Xb, labels):
+    """For wide, deep nets: every stage is checked on the inputs the GPU itself
+    used (its stored activations and logits), so that units whose activation
+    sits within one rounding of zero are decided the same way on both sides."""
+    from oracle import dense
+    H = [Xb] + gpu_hidden(job)
+    gWm, gWb, glogits, gloss = job.gpu_state()
+    for l, (h_in, wb) in enumerate(zip(H, job.Wb)):                  # forward, layer by layer
+        last = l + 1 == len(job.Wb)
+        ref = dense.dense_bf16(h_in, wb, dense.ACT_NONE if last else dense.ACT_RELU)
+        got = glogits if last else synth.bf16_bits_to_f32(H[l + 1])
+        if not last:
+            ref = synth.bf16_bits_to_f32(dense.round_bf16(ref))
+        if last:
+            assert norm_rel_err(got, ref) < 1e-5, (job.job, "logits")           # float sums against double
+        else:
+            assert norm_rel_err(got, ref) < 2.0 ** -7, (job.job, "forward", l)  # at most bf16 flips
+            assert (got != ref).mean() < 2e-3, (job.job, "forward flips", l)
+    before = [w.copy() for w in job.Wm]
+    loss, grads, G = train.backward_update(H, glogits, labels, job.Wm, job.Wb, job.lr)
+    assert abs(gloss - loss) < 1e-4 * max(1.0, abs(loss))
+    for l, (g, wm_gpu, w0) in enumerate(zip(grads, gWm, before)):
+        gmax = np.abs(g).max()
+        g_gpu = (w0.astype(np.float64) - wm_gpu.astype(np.float64)) / float(job.lr)
+        slack = np.spacing(np.abs(w0).max()) / float(job.lr)
+        assert np.abs(g_gpu - g).max() < TOL_GRAD * gmax + 2 * slack, (job.job, "dW", l)
+        assert np.array_equal(gWb[l], synth.f32_to_bf16_bits(wm_gpu)), (job.job, "Wb", l)
+
+
+def check_step(job, Xb, labels, step, tol_grad=TOL_GRAD):
     before = [w.copy() for w in job.Wm]
     loss, logits, grads = train.train_step(Xb, labels, job.Wm, job.Wb, job.lr)    # oracle, in place
     gWm, gWb, glogits, gloss = job.gpu_state()
@@ -90,8 +134,8 @@ def check_step(job, Xb, labels, step):
             g_gpu = (w0.astype(np.float64) - wm_gpu.astype(np.float64)) / float(job.lr)
             # recovering the gradient from the update is limited by the float spacing of W
             slack = np.spacing(np.abs(w0).max()) / float(job.lr)
-            assert np.abs(g_gpu - g).max() < TOL_GRAD * gmax + 2 * slack, (tag, l)
-        bound = float(job.lr) * TOL_GRAD * gmax + np.spacing(np.abs(wm_ref).max())
+            assert np.abs(g_gpu - g).max() < tol_grad * gmax + 2 * slack, (tag, l)
+        bound = float(job.lr) * tol_grad * gmax + np.spacing(np.abs(wm_ref).max())
         assert np.abs(wm_gpu - wm_ref).max() <= bound, (tag, l, np.abs(wm_gpu - wm_ref).max(), bound)
         assert np.array_equal(wb_gpu, synth.f32_to_bf16_bits(wm_gpu)), (tag, l)   # working copy = bf16(master)
         diff = wb_gpu != wb_ref
