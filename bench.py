@@ -43,6 +43,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-switch", action="store_true", help="skip the evict/restore/compaction figures")
+    ap.add_argument("--no-training", action="store_true", help="skip the packed training-step figures")
     ap.add_argument("--hot-only", action="store_true", help="only the timed packed-iteration loop (for profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -158,7 +159,7 @@ def main():
     log(f"pool {cap / 1e9:.2f} GB, {MODELS} models resident, {rounds} rounds planned")
     main_res = run(poisson, batches, "poisson")
     if args.hot_only:
-        sat = None
+        sat = run(saturated, [np.full(MODELS, MAX_BATCH)] * rounds, "saturated")
         # a plain copy of known size in the same process: scale for profiler byte counters
         cal = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
         for _ in range(3):
@@ -238,7 +239,76 @@ def main():
     # ---------------------------------------------------------------- switch path
     if not args.no_switch and not args.hot_only:
         out["switch"] = switch_figures(torch, salus, stream)
+    if not args.no_training and not args.hot_only:
+        out["training"] = training_figures(torch, salus, stream)
     print(json.dumps(out), flush=True)
+
+
+def training_figures(torch, salus, stream, jobs=8, dims=(2048, 2048, 2048, 2048, 1000), M=64,
+                     steps=50, warmup=5):
+    """Hyper-parameter-tuning packing: 8 training jobs of one architecture, one
+    packed step = schedule + forward + loss + backward + SGD for all of them."""
+    up = lambda v: (v + 255) // 256 * 256
+    layers, off = [], 0
+    for k, n in zip(dims[:-1], dims[1:]):
+        layers.append((k, n, off, off + up(k * n * 2)))
+        off += up(k * n * 2) + up(k * n * 4)
+    P = off
+    x_off, labels_off = 0, up(M * dims[0] * 2)
+    logits_off = labels_off + up(M * 4)
+    loss_off = logits_off + up(M * dims[-1] * 4)
+    work_off = loss_off + 256
+    E = up(work_off + salus.train_work_bytes(M, layers))
+    cap = jobs * (P + E)
+    buf = torch.empty(cap, dtype=torch.uint8, device="cuda:0")
+    pool = salus.Pool(buf.data_ptr(), cap, policy=salus.POLICY_PACK, stream=stream)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(2)
+    items = []
+    for j in range(jobs):
+        st, jid = pool.lane_alloc(P, E, 0, 10 ** 9)
+        assert st == salus.OK
+        q = pool.job_query(jid)
+        for k, n, wb, wm in layers:
+            w = torch.randn(k, n, generator=gen, device="cuda:0") * (1.0 / k ** 0.5)
+            buf[q.persist_off + wm:q.persist_off + wm + k * n * 4].copy_(w.view(torch.uint8).reshape(-1))
+            buf[q.persist_off + wb:q.persist_off + wb + k * n * 2].copy_(
+                w.to(torch.bfloat16).view(torch.uint8).reshape(-1))
+        x = torch.randn(M, dims[0], generator=gen, device="cuda:0").to(torch.bfloat16)
+        y = torch.randint(0, dims[-1], (M,), generator=gen, device="cuda:0", dtype=torch.int32)
+        buf[q.lane_off + x_off:q.lane_off + x_off + M * dims[0] * 2].copy_(x.view(torch.uint8).reshape(-1))
+        buf[q.lane_off + labels_off:q.lane_off + labels_off + M * 4].copy_(y.view(torch.uint8).reshape(-1))
+        lr = 10.0 ** (-4.0 + 3.0 * j / max(jobs - 1, 1))          # log-spaced in [1e-4, 1e-1]
+        items.append(dict(job=jid, M=M, lr=lr, layers=layers, x_off=x_off, labels_off=labels_off,
+                          logits_off=logits_off, loss_off=loss_off, work_off=work_off))
+    descs, keep = salus.Pool.make_train_descs(items)
+    slots = (salus.Slot * jobs)()
+
+    def step():
+        assert pool.schedule_into(slots, jobs) == jobs
+        assert pool.grouped_train_step(descs, jobs, stream) == salus.OK
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    params = sum(k * n for k, n, _, _ in layers)
+    flops = jobs * 2.0 * M * (3 * params - layers[0][0] * layers[0][1])
+    # bf16 weights read by forward and by the input gradient (not layer 1), master read + written,
+    # bf16 copy rewritten; activations are a few MB and left out
+    alg_bytes = jobs * (2 * params + 2 * (params - layers[0][0] * layers[0][1]) + 8 * params + 2 * params)
+    loss = buf[pool.job_query(0).lane_off + loss_off:][:4].view(torch.float32).item()
+    res = {"workload": f"{jobs} training jobs, MLP {'-'.join(map(str, dims))}, batch {M}, bf16 + float master, SGD",
+           "ms_per_step": round(wall * 1e3, 4), "tflops": round(flops / wall / 1e12, 2),
+           "hbm_gbs": round(alg_bytes / wall / 1e9, 1), "hbm_frac": round(alg_bytes / wall / 1e9 / HBM_PEAK_GBS, 4),
+           "launches_per_step": 12, "loss_job0_after": round(loss, 4)}
+    log(f"[training] {res}")
+    pool.close()
+    return res
 
 
 def switch_figures(torch, salus, stream):

@@ -11,13 +11,13 @@ LIB = os.path.join(HERE, "libsalus.so")
 SOURCES = ["api.hip", "kernels_copy.hip", "kernels_gemm.hip", "kernels_train.hip", "pool_core.cpp"]
 
 
-def build(verbose=False):
+def build(verbose=False, extra_flags=(), out=LIB):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-result",
+           "-Wall", "-Wno-unused-result", *extra_flags,
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+           "-o", out] + [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd))
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -27,7 +27,7 @@ def build(verbose=False):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -29,6 +29,10 @@ struct GroupArgs {
 constexpr int kGemmThreads = 256;
 constexpr int kWaves = 4;
 
+#ifndef SALUS_BF16_ATTR
+#define SALUS_BF16_ATTR
+#endif
+
 __device__ inline float activate(float z, uint32_t act)
 {
     if (act == 1) return fmaxf(z, 0.0f);
@@ -136,7 +140,7 @@ constexpr int reduce_lds_floats() { return kWaves * 3 * (NACC < 16 ? NACC : 16) 
 // output column n0+8c+i are contiguous in row n0+8c+i and are loaded as they are.
 // ---------------------------------------------------------------------------
 template <int MT, bool TW>
-__global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
+__global__ __launch_bounds__(kGemmThreads) SALUS_BF16_ATTR void grouped_dense_bf16(GroupArgs a)
 {
     constexpr int TM = 16 * MT, TN = 128, NACC = MT * 8;
     __shared__ float lds[reduce_lds_floats<NACC>()];
@@ -144,7 +148,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
     const Problem &p = a.p[tile.problem];
     const uint32_t M = p.M, K = p.K, N = p.N;
     const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t ncol = tile.n0 + 8 * c;
     const bool col_ok = ncol < N;
     const uint16_t *W = (const uint16_t *)p.W;
@@ -157,21 +161,32 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
     const int nsteps = (int)((K + 31) / 32);
     const u32x4 zero = {0u, 0u, 0u, 0u};
 
-    auto load = [&](int s, u32x4 (&w)[8], u32x4 (&x)[MT]) {
+    // Loads are never predicated: a lane whose block lies outside the matrix
+    // reads a clamped, valid address instead and its values are dropped later
+    // (rows >= M and columns >= N are never stored; k-groups >= K get a zero A
+    // operand).  With no branch around any load the compiler can count exactly
+    // how many loads may stay in flight at each use, which is what keeps the
+    // next step's loads outstanding while this step is multiplied.
+    const uint32_t ncol_c = col_ok ? ncol : 0u;
+    auto load = [&](int s, u32x4 (&w)[8], u32x4 (&x)[MT], bool &k_ok) {
         const uint32_t kb = 32u * (uint32_t)s + 8u * (uint32_t)g;
-        const bool k_ok = s < nsteps && kb < K;
+        k_ok = kb < K;
+        const uint32_t kc = k_ok ? kb : 0u;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            const uint16_t *at = TW ? W + (size_t)(ncol + r) * K + kb : W + (size_t)(kb + r) * N + ncol;
-            w[r] = (k_ok && col_ok) ? __builtin_nontemporal_load((const u32x4 *)at) : zero;
+            const uint16_t *at = TW ? W + (size_t)(ncol_c + r) * K + kc : W + (size_t)(kc + r) * N + ncol_c;
+            w[r] = __builtin_nontemporal_load((const u32x4 *)at);
         }
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             const uint32_t row = tile.m0 + 16 * t + c;
-            x[t] = (k_ok && row < M) ? *(const u32x4 *)(X + (size_t)row * K + kb) : zero;
+            x[t] = *(const u32x4 *)(X + (size_t)(row < M ? row : M - 1) * K + kc);
         }
     };
-    auto compute = [&](const u32x4 (&w)[8], const u32x4 (&x)[MT]) {
+    auto compute = [&](const u32x4 (&w)[8], const u32x4 (&xr)[MT], bool k_ok) {
+        u32x4 x[MT];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) x[t] = k_ok ? xr[t] : zero;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             // column i of the 8x8 block: dword j = (row 2j, row 2j+1)
@@ -192,17 +207,33 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
         }
     };
 
-    // the four wavefronts take k-steps wave, wave+4, ...; two steps stay in flight
+    // The four wavefronts take k-steps wave, wave+4, ...: this wavefront owns
+    // `mine` steps.  Two steps are in flight at any time; the last (up to three)
+    // steps are peeled so that the main loop never loads past the end.
     u32x4 w0[8], w1[8], x0[MT], x1[MT];
-    int s = wave;
-    load(s, w0, x0);
-    load(s + kWaves, w1, x1);
-    for (; s < nsteps; s += 2 * kWaves) {
-        compute(w0, x0);
-        load(s + 2 * kWaves, w0, x0);
-        compute(w1, x1);
-        load(s + 3 * kWaves, w1, x1);
+    bool ok0, ok1;
+    const int mine = nsteps > wave ? (nsteps - wave + kWaves - 1) / kWaves : 0;
+    auto step = [&](int i) { return wave + kWaves * i; };
+    load(step(0), w0, x0, ok0);
+    load(step(1), w1, x1, ok1);
+    int i = 0;
+    for (; i + 3 < mine; i += 2) {
+        // keep the instruction scheduler from sinking the loads below the next
+        // multiply phase: each phase must stay where it is written
+        compute(w0, x0, ok0);
+        __builtin_amdgcn_sched_barrier(0);
+        load(step(i + 2), w0, x0, ok0);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(w1, x1, ok1);
+        __builtin_amdgcn_sched_barrier(0);
+        load(step(i + 3), w1, x1, ok1);
+        __builtin_amdgcn_sched_barrier(0);
     }
+    const int left = mine - i;
+    if (left >= 1) compute(w0, x0, ok0);
+    if (left == 3) load(step(i + 2), w0, x0, ok0);
+    if (left >= 2) compute(w1, x1, ok1);
+    if (left == 3) compute(w0, x0, ok0);
 
     float own[NACC];
     reduce_scatter<NACC>(acc, own, lds);
@@ -253,7 +284,7 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_f32(GroupArgs a)
     const Problem &p = a.p[tile.problem];
     const uint32_t M = p.M, K = p.K, N = p.N;
     const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t ncol = tile.n0 + 4 * c;
     const bool col_ok = ncol < N;
     const float *W = (const float *)p.W;
@@ -266,19 +297,24 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_f32(GroupArgs a)
     const int nsteps = (int)((K + 15) / 16);
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
-    auto load = [&](int s, f32x4 (&w)[4], f32x4 (&x)[MT]) {
+    // unpredicated loads from clamped addresses, as in the bf16 kernel
+    const uint32_t ncol_c = col_ok ? ncol : 0u;
+    auto load = [&](int s, f32x4 (&w)[4], f32x4 (&x)[MT], bool &k_ok) {
         const uint32_t kb = 16u * (uint32_t)s + 4u * (uint32_t)g;
-        const bool k_ok = s < nsteps && kb < K;
+        k_ok = kb < K;
+        const uint32_t kc = k_ok ? kb : 0u;
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            w[q] = (k_ok && col_ok) ? *(const f32x4 *)(W + (size_t)(kb + q) * N + ncol) : zero;
+        for (int q = 0; q < 4; ++q) w[q] = *(const f32x4 *)(W + (size_t)(kc + q) * N + ncol_c);
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             const uint32_t row = tile.m0 + 16 * t + c;
-            x[t] = (k_ok && row < M) ? *(const f32x4 *)(X + (size_t)row * K + kb) : zero;
+            x[t] = *(const f32x4 *)(X + (size_t)(row < M ? row : M - 1) * K + kc);
         }
     };
-    auto compute = [&](const f32x4 (&w)[4], const f32x4 (&x)[MT]) {
+    auto compute = [&](const f32x4 (&w)[4], const f32x4 (&xr)[MT], bool k_ok) {
+        f32x4 x[MT];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) x[t] = k_ok ? xr[t] : zero;
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -290,15 +326,29 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_f32(GroupArgs a)
     };
 
     f32x4 w0[4], w1[4], x0[MT], x1[MT];
-    int s = wave;
-    load(s, w0, x0);
-    load(s + kWaves, w1, x1);
-    for (; s < nsteps; s += 2 * kWaves) {
-        compute(w0, x0);
-        load(s + 2 * kWaves, w0, x0);
-        compute(w1, x1);
-        load(s + 3 * kWaves, w1, x1);
+    bool ok0, ok1;
+    const int mine = nsteps > wave ? (nsteps - wave + kWaves - 1) / kWaves : 0;
+    auto step = [&](int i) { return wave + kWaves * i; };
+    load(step(0), w0, x0, ok0);
+    load(step(1), w1, x1, ok1);
+    int i = 0;
+    for (; i + 3 < mine; i += 2) {
+        // keep the instruction scheduler from sinking the loads below the next
+        // multiply phase: each phase must stay where it is written
+        compute(w0, x0, ok0);
+        __builtin_amdgcn_sched_barrier(0);
+        load(step(i + 2), w0, x0, ok0);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(w1, x1, ok1);
+        __builtin_amdgcn_sched_barrier(0);
+        load(step(i + 3), w1, x1, ok1);
+        __builtin_amdgcn_sched_barrier(0);
     }
+    const int left = mine - i;
+    if (left >= 1) compute(w0, x0, ok0);
+    if (left == 3) load(step(i + 2), w0, x0, ok0);
+    if (left >= 2) compute(w1, x1, ok1);
+    if (left == 3) compute(w0, x0, ok0);
 
     float own[NACC];
     reduce_scatter<NACC>(acc, own, lds);
