@@ -68,7 +68,8 @@ def main():
     P = sum(w_sizes)
     x_off, y_off = 0, up(MAX_BATCH * DIMS[0] * 2)
     h_off = y_off + up(MAX_BATCH * DIMS[-1] * 4)
-    E = up(h_off + 2 * up(MAX_BATCH * max(DIMS[1:-1]) * 2))
+    E = up(h_off + salus.forward_work_bytes(
+        MAX_BATCH, [(k, n, 0, 0) for k, n in zip(DIMS[:-1], DIMS[1:])], salus.BF16))
     cap = MODELS * (P + E)
     buf = torch.empty(cap, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream

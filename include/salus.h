@@ -105,10 +105,11 @@ typedef struct {
 
 /* One job's forward pass in a packed iteration.  All three offsets are inside
  * the job's lane (its ephemeral memory).  x: input, M x K_0, in `dtype`.
- * y: output of the last layer, M x N_last, always float.  h: room for the
- * intermediate activations, 2 * M * max_l(N_l) elements of `dtype` (unused
- * with a single layer).  SALUS_BF16: weights, input and intermediate
- * activations are bf16 (activations rounded to nearest-even), sums in float. */
+ * y: output of the last layer, M x N_last, always float.  h: scratch of
+ * salus_forward_work_bytes() bytes for the intermediate activations, whose
+ * layout is private to the library.  SALUS_BF16: weights, input and
+ * intermediate activations are bf16 (activations rounded to nearest-even),
+ * sums in float. */
 typedef struct {
     int32_t  job;
     uint32_t M;
@@ -117,6 +118,10 @@ typedef struct {
     const salus_layer *layers;   /* host pointer, n_layers entries */
     uint64_t x_off, y_off, h_off;
 } salus_gemm_desc;
+
+/* Bytes of lane scratch (`h`) a forward pass of these layers needs at batch M. */
+uint64_t salus_forward_work_bytes(uint32_t M, const salus_layer *layers, uint32_t n_layers,
+                                  int32_t dtype);
 
 typedef struct {
     uint64_t rounds, iterations;

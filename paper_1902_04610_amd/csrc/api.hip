@@ -220,6 +220,27 @@ static bool overlap(uint64_t a, uint64_t an, uint64_t b, uint64_t bn)
     return an && bn && a < b + bn && b < a + an;
 }
 
+static uint64_t up256(uint64_t v) { return (v + 255) & ~(uint64_t)255; }
+
+// Scratch of a forward pass inside the lane: two row-major buffers of M x (widest
+// hidden layer) that the layers write and read alternately.
+static void forward_scratch(uint32_t M, const salus_layer *layers, uint32_t n_layers, int32_t dtype,
+                            uint64_t *xp_bytes, uint64_t *h_stride)
+{
+    uint32_t max_n = 0;
+    for (uint32_t l = 0; l + 1 < n_layers; ++l) max_n = std::max(max_n, layers[l].N);
+    *xp_bytes = 0;
+    *h_stride = up256((uint64_t)M * max_n * (dtype == SALUS_BF16 ? 2 : 4));
+}
+
+uint64_t salus_forward_work_bytes(uint32_t M, const salus_layer *layers, uint32_t n_layers, int32_t dtype)
+{
+    if (!layers || n_layers == 0 || M == 0) return 0;
+    uint64_t xp, hs;
+    forward_scratch(M, layers, n_layers, dtype, &xp, &hs);
+    return xp + (n_layers > 1 ? 2 * hs : 0);
+}
+
 int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
                               void *stream)
 {
@@ -230,7 +251,7 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
     char *base = pool->ops.base;
     uint32_t depth = 0;
     std::vector<int32_t> lanes_used;
-    struct Resolved { char *w, *x, *y, *h; uint64_t hstride; uint32_t esz; };
+    struct Resolved { char *w, *x, *y, *xp, *h; uint64_t hstride; };
     std::vector<Resolved> res(n);
     for (uint32_t i = 0; i < n; ++i) {
         const salus_gemm_desc &d = descs[i];
@@ -248,7 +269,6 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
         const uint32_t mult = 16 / esz;
         uint64_t lane_size = 0;
         const uint64_t lane_off = pool->core->lane_base(j->lane, &lane_size);
-        uint32_t max_n = 0;
         for (uint32_t l = 0; l < d.n_layers; ++l) {
             const salus_layer &L = d.layers[l];
             if (L.K == 0 || L.N == 0 || L.K % mult || L.N % mult)
@@ -258,22 +278,24 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
             const uint64_t wbytes = (uint64_t)L.K * L.N * esz;
             if (L.w_off % 16 || L.w_off > j->P || wbytes > j->P - L.w_off)
                 return set_error(pool, SALUS_EINVAL, "weights outside the persistent block");
-            if (l + 1 < d.n_layers) max_n = std::max(max_n, L.N);
         }
         const uint64_t xbytes = (uint64_t)d.M * d.layers[0].K * esz;
         const uint64_t ybytes = (uint64_t)d.M * d.layers[d.n_layers - 1].N * 4;
-        const uint64_t hstride = ((uint64_t)d.M * max_n * esz + 255) & ~(uint64_t)255;
-        const uint64_t hbytes = d.n_layers > 1 ? 2 * hstride : 0;
+        uint64_t xp_bytes, hstride;
+        forward_scratch(d.M, d.layers, d.n_layers, d.dtype, &xp_bytes, &hstride);
+        const uint64_t hbytes = xp_bytes + (d.n_layers > 1 ? 2 * hstride : 0);
         auto inside = [&](uint64_t off, uint64_t nb) { return off % 16 == 0 && off <= lane_size && nb <= lane_size - off; };
         if (!inside(d.x_off, xbytes) || !inside(d.y_off, ybytes) || !inside(d.h_off, hbytes))
             return set_error(pool, SALUS_EINVAL, "buffer outside the job's lane");
         if (overlap(d.x_off, xbytes, d.y_off, ybytes) || overlap(d.x_off, xbytes, d.h_off, hbytes) ||
             overlap(d.y_off, ybytes, d.h_off, hbytes))
             return set_error(pool, SALUS_EINVAL, "x, y and h ranges overlap");
-        res[i] = {base + j->off, base + lane_off + d.x_off, base + lane_off + d.y_off,
-                  base + lane_off + d.h_off, hstride, esz};
+        char *lane = base + lane_off;
+        res[i] = {base + j->off, lane + d.x_off, lane + d.y_off, lane + d.h_off,
+                  lane + d.h_off + xp_bytes, hstride};
         depth = std::max(depth, d.n_layers);
     }
+    hipStream_t s = (hipStream_t)stream;
     // one grouped launch per layer depth over all jobs that have that layer
     std::vector<Problem> probs;
     for (int dt = SALUS_F32; dt <= SALUS_BF16; ++dt) {
@@ -284,6 +306,7 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
                 if (d.dtype != dt || l >= d.n_layers) continue;
                 const salus_layer &L = d.layers[l];
                 const bool last = l + 1 == d.n_layers;
+                const bool bf = dt == SALUS_BF16;
                 Problem pr{};
                 pr.W = res[i].w + L.w_off;
                 pr.X = l == 0 ? res[i].x : res[i].h + ((l - 1) & 1) * res[i].hstride;
@@ -291,20 +314,21 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
                 pr.M = d.M;
                 pr.K = L.K;
                 pr.N = L.N;
-                pr.flags = (uint32_t)L.act | ((!last && dt == SALUS_BF16) ? kOutBf16 : 0u);
+                pr.flags = (uint32_t)L.act;
+                if (bf && !last) pr.flags |= kOutBf16;
                 probs.push_back(pr);
             }
             if (probs.empty()) continue;
             hipError_t e = dt == SALUS_BF16
-                               ? launch_grouped_bf16(probs.data(), (uint32_t)probs.size(), false, (hipStream_t)stream, &pool->gemm_launches)
-                               : launch_grouped_f32(probs.data(), (uint32_t)probs.size(), (hipStream_t)stream, &pool->gemm_launches);
+                               ? launch_grouped_bf16(probs.data(), (uint32_t)probs.size(), false, s, &pool->gemm_launches)
+                               : launch_grouped_f32(probs.data(), (uint32_t)probs.size(), s, &pool->gemm_launches);
             if (e != hipSuccess) return set_error(pool, SALUS_EHIP, hipGetErrorString(e));
         }
     }
     return SALUS_OK;
 }
 
-static uint64_t up256(uint64_t v) { return (v + 255) & ~(uint64_t)255; }
+
 
 // Scratch layout of a training step inside the lane: H_1 .. H_{L-1} (bf16, kept
 // for the backward pass), then two gradient buffers of M x max_l(N_l) bf16.

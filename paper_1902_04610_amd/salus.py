@@ -88,6 +88,7 @@ _PROTOS = {
     "salus_schedule_iteration": [C.c_void_p, C.POINTER(Slot), C.c_uint32, C.POINTER(C.c_uint32)],
     "salus_grouped_forward": [C.c_void_p, C.POINTER(GemmDesc), C.c_uint32, C.c_void_p],
     "salus_train_work_bytes": [C.c_uint32, C.POINTER(TrainLayer), C.c_uint32],
+    "salus_forward_work_bytes": [C.c_uint32, C.POINTER(Layer), C.c_uint32, C.c_int32],
     "salus_grouped_train_step": [C.c_void_p, C.POINTER(TrainDesc), C.c_uint32, C.c_void_p],
     "salus_switch_out": [C.c_void_p, C.c_int32, C.c_void_p],
     "salus_switch_in": [C.c_void_p, C.c_int32],
@@ -120,7 +121,7 @@ def lib():
             fn = getattr(L, name)
             fn.argtypes = args
             fn.restype = (C.c_char_p if name == "salus_last_error" else
-                          C.c_uint64 if name == "salus_train_work_bytes" else C.c_int32)
+                          C.c_uint64 if name.endswith("_work_bytes") else C.c_int32)
         _lib = L
     return _lib
 
@@ -280,6 +281,12 @@ class Pool:
         n = C.c_uint32()
         self._lib.salus_poll_events(self._h, ev, cap, C.byref(n))
         return [(ev[i].kind, ev[i].a, ev[i].b) for i in range(n.value)]
+
+
+def forward_work_bytes(M, layers, dtype):
+    """layers: [(K, N, w_off, act)]"""
+    L = (Layer * len(layers))(*[Layer(K, N, w, a, 0) for (K, N, w, a) in layers])
+    return lib().salus_forward_work_bytes(M, L, len(layers), dtype)
 
 
 def train_work_bytes(M, layers):

@@ -54,6 +54,6 @@ def mlp_layout(dims, esz, M):
     x_off = 0
     y_off = up(M * dims[0] * esz)
     h_off = y_off + up(M * dims[-1] * 4)
-    max_n = max(dims[1:-1], default=0)
-    E = h_off + 2 * up(M * max_n * esz)
+    layers = [(K, N, 0, 0) for K, N in zip(dims[:-1], dims[1:])]
+    E = h_off + salus.forward_work_bytes(M, layers, salus.BF16 if esz == 2 else salus.F32)
     return w_offs, P, x_off, y_off, h_off, max(E, 256)

@@ -45,7 +45,8 @@ def test_workload2_full_size_sampled_outputs():
     P = sum(w_sizes)
     x_off, y_off = 0, up(32 * DIMS[0] * 2)
     h_off = y_off + up(32 * DIMS[-1] * 4)
-    E = up(h_off + 2 * up(32 * 4096 * 2))
+    E = up(h_off + salus.forward_work_bytes(32, [(k, n, 0, 0) for k, n in zip(DIMS[:-1], DIMS[1:])],
+                                            salus.BF16))
     dp = big_pool(MODELS * (P + E), policy=salus.POLICY_PACK)
     o = op.Pool(MODELS * (P + E), policy=op.PACK)
     gen = torch.Generator(device="cuda")
