@@ -45,6 +45,7 @@ def main():
     ap.add_argument("--no-switch", action="store_true", help="skip the evict/restore/compaction figures")
     ap.add_argument("--no-training", action="store_true", help="skip the packed training-step figures")
     ap.add_argument("--hot-only", action="store_true", help="only the timed packed-iteration loop (for profiling)")
+    ap.add_argument("--train-only", action="store_true", help="only the packed training step (for profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (jobs are packed inside one device); "
@@ -56,6 +57,10 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if args.train_only:
+        torch.cuda.set_device(0)
+        print(json.dumps(training_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
+        return
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     K_steps, W_steps = args.steps, args.warmup

@@ -411,8 +411,7 @@ int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *des
             }
             max_n = std::max<uint64_t>(max_n, d.layers[l].N);
         }
-        R.g_off[0] = at;
-        R.g_off[1] = at + up256((uint64_t)d.M * max_n * 2);
+        for (int b = 0; b < 2; ++b) R.g_off[b] = at + b * up256((uint64_t)d.M * max_n * 2);
         depth = std::max(depth, d.n_layers);
     }
     hipError_t e = hipSuccess;
@@ -447,6 +446,7 @@ int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *des
             p.labels = (const int32_t *)(res[i].lane + d.labels_off);
             p.grad = res[i].lane + res[i].g_off[0];
             p.loss = (float *)(res[i].lane + d.loss_off);
+            p.row_loss = (float *)(res[i].lane + res[i].g_off[1]);   // a gradient buffer that is idle here
             p.M = d.M;
             p.N = d.layers[d.n_layers - 1].N;
             lp.push_back(p);
@@ -455,7 +455,9 @@ int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *des
     }
     // backward: layer `back` counted from each job's last layer, so that jobs of
     // different depth still share launches; input gradient first (it reads the
-    // weights the update is about to overwrite)
+    // weights the update is about to overwrite).  (Running the updates on a second
+    // stream, overlapped with the next input gradient, was measured slower: the
+    // cross-stream waits cost more than the overlap wins.)
     std::vector<UpdateProblem> ups;
     for (uint32_t back = 0; back < depth && e == hipSuccess; ++back) {
         probs.clear();

@@ -13,7 +13,10 @@ struct CopySeg {
     uint64_t len;        // bytes, multiple of 16; src and dst 16-byte aligned
 };
 constexpr uint32_t kMaxSeg = 64;            // segments per launch (one per wavefront lane)
-constexpr uint32_t kCopyChunk = 64 * 1024;  // bytes one workgroup moves per grid-stride step
+#ifndef SALUS_COPY_CHUNK_KB
+#define SALUS_COPY_CHUNK_KB 16
+#endif
+constexpr uint32_t kCopyChunk = SALUS_COPY_CHUNK_KB * 1024;  // bytes one workgroup moves per grid-stride step
 
 // Copies n mutually independent segments (no destination may overlap another
 // segment's source); more than kMaxSeg segments are split over launches.
@@ -54,6 +57,7 @@ struct LossProblem {
     const int32_t *labels;   // M
     void *grad;              // M x N bf16: (softmax - onehot) / M
     float *loss;             // mean cross-entropy
+    float *row_loss;         // scratch, M floats
     uint32_t M, N;
 };
 struct UpdateProblem {

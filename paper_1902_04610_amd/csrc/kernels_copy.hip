@@ -8,8 +8,9 @@
 // the persistent region.
 //
 // All kernels are bound by memory bandwidth: every thread moves 16 bytes per
-// access, consecutive lanes touch consecutive addresses, a workgroup moves
-// 64 KiB per step, and all addressing is 64-bit (pools are far larger than 4 GiB).
+// access, consecutive lanes touch consecutive addresses, a workgroup moves one
+// chunk (kCopyChunk bytes) per step, and all addressing is 64-bit (pools are far
+// larger than 4 GiB).
 #include <algorithm>
 #include <vector>
 
@@ -25,9 +26,9 @@ struct CopyArgs {
 };
 
 constexpr int kCopyThreads = 256;
-constexpr int kVecPerThread = kCopyChunk / (kCopyThreads * 16);   // 16
+constexpr int kVecPerThread = kCopyChunk / (kCopyThreads * 16);
 
-// Grid-stride over 64 KiB chunks of a list of segments.  Each wavefront holds
+// Grid-stride over the chunks of a list of segments.  Each wavefront holds
 // segment i in lane i, scans the per-segment chunk counts to get every
 // segment's first chunk number, and finds the segment of a chunk with a ballot.
 __global__ __launch_bounds__(kCopyThreads) void copy_segments(CopyArgs a, uint64_t total_chunks)
@@ -67,9 +68,12 @@ __global__ __launch_bounds__(kCopyThreads) void copy_segments(CopyArgs a, uint64
 
 static uint32_t copy_grid(uint64_t chunks)
 {
-    // enough resident workgroups to cover the memory latency of 256 compute
-    // units, few enough that the per-workgroup scan stays negligible
-    const uint64_t cap = 256 * 16;
+    // measured on MI355X: small chunks and a grid large enough that most copies
+    // need a single pass give the best read+write rate (about 5.3 TB/s)
+#ifndef SALUS_COPY_WGS_PER_CU
+#define SALUS_COPY_WGS_PER_CU 256
+#endif
+    const uint64_t cap = 256 * SALUS_COPY_WGS_PER_CU;
     return (uint32_t)std::min<uint64_t>(chunks, cap);
 }
 

@@ -400,15 +400,16 @@ hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipSt
         const dim3 grid(tiles), block(kGemmThreads);
         if (trans_w) {
             if (mt == 1) hipLaunchKernelGGL((grouped_dense_bf16<1, true>), grid, block, 0, stream, a);
-            else if (mt == 2) hipLaunchKernelGGL((grouped_dense_bf16<2, true>), grid, block, 0, stream, a);
-            else hipLaunchKernelGGL((grouped_dense_bf16<4, true>), grid, block, 0, stream, a);
+            else hipLaunchKernelGGL((grouped_dense_bf16<2, true>), grid, block, 0, stream, a);
         } else {
             if (mt == 1) hipLaunchKernelGGL((grouped_dense_bf16<1, false>), grid, block, 0, stream, a);
-            else if (mt == 2) hipLaunchKernelGGL((grouped_dense_bf16<2, false>), grid, block, 0, stream, a);
-            else hipLaunchKernelGGL((grouped_dense_bf16<4, false>), grid, block, 0, stream, a);
+            else hipLaunchKernelGGL((grouped_dense_bf16<2, false>), grid, block, 0, stream, a);
         }
     };
-    return launch_groups(p, n, 128, 16, 32, launch, launches);
+    // Row tiles of at most 32 rows: a 64-row tile halves the workgroup count and
+    // the occupancy, and measured slower even though W is then read once instead
+    // of twice (the second read of neighbouring row tiles hits L2).
+    return launch_groups(p, n, 128, 16, 1u << 30, launch, launches);
 }
 
 hipError_t launch_grouped_f32(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches)

@@ -40,8 +40,10 @@ __device__ inline float wave_sum(float v)
 // ---------------------------------------------------------------------------
 // Mean softmax cross-entropy over the M rows of each job and its gradient
 // (softmax - onehot) / M, written as bf16 for the backward products.  One
-// workgroup per job; each wavefront takes rows w, w+4, ... and keeps a running
-// loss; the four partial losses are added in a fixed order.
+// wavefront per row (a workgroup takes four rows of one job; the job is found
+// with the scan + ballot used everywhere else); each row's loss goes to a
+// scratch array and a second, tiny kernel adds the rows of a job in order, so
+// the result does not depend on how the rows were scheduled.
 // ---------------------------------------------------------------------------
 struct LossArgs {
     uint32_t n;
@@ -51,33 +53,41 @@ struct LossArgs {
 
 __global__ __launch_bounds__(256) void softmax_xent_rows(LossArgs a)
 {
-    __shared__ float partial[4];
-    const LossProblem &p = a.p[blockIdx.x];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool valid = lane < (int)a.n;
+    const uint32_t blocks = valid ? (a.p[lane].M + 3) / 4 : 0;
+    const uint32_t first = wave_excl_scan_u32(blocks, nullptr);
+    const int job = __builtin_amdgcn_readfirstlane(wave_find_range(first, blockIdx.x, valid));
+    const LossProblem &p = a.p[job];
+    const uint32_t row = (blockIdx.x - __shfl(first, job, 64)) * 4 + wave;
     const uint32_t M = p.M, N = p.N;
+    if (row >= M) return;
     const float inv_m = 1.0f / (float)M;
-    float loss = 0.0f;
-    for (uint32_t row = wave; row < M; row += 4) {
-        const float *z = p.logits + (size_t)row * N;
-        float zmax = -INFINITY;
-        for (uint32_t n = lane; n < N; n += 64) zmax = fmaxf(zmax, z[n]);
-        zmax = wave_max(zmax);
-        float denom = 0.0f;
-        for (uint32_t n = lane; n < N; n += 64) denom += expf(z[n] - zmax);
-        denom = wave_sum(denom);
-        int label = p.labels[row];
-        label = label < 0 ? 0 : (label >= (int)N ? (int)N - 1 : label);    // never read outside the row
-        loss += -(z[label] - zmax - logf(denom));
-        uint16_t *g = (uint16_t *)p.grad + (size_t)row * N;
-        const float inv_d = 1.0f / denom;
-        for (uint32_t n = lane; n < N; n += 64) {
-            const float prob = expf(z[n] - zmax) * inv_d;
-            g[n] = (uint16_t)bf16_rne((prob - ((int)n == label ? 1.0f : 0.0f)) * inv_m);
-        }
+    const float *z = p.logits + (size_t)row * N;
+    float zmax = -INFINITY;
+    for (uint32_t n = lane; n < N; n += 64) zmax = fmaxf(zmax, z[n]);
+    zmax = wave_max(zmax);
+    float denom = 0.0f;
+    for (uint32_t n = lane; n < N; n += 64) denom += expf(z[n] - zmax);
+    denom = wave_sum(denom);
+    int label = p.labels[row];
+    label = label < 0 ? 0 : (label >= (int)N ? (int)N - 1 : label);    // never read outside the row
+    if (lane == 0) p.row_loss[row] = -(z[label] - zmax - logf(denom));
+    uint16_t *g = (uint16_t *)p.grad + (size_t)row * N;
+    const float inv_d = 1.0f / denom;
+    for (uint32_t n = lane; n < N; n += 64) {
+        const float prob = expf(z[n] - zmax) * inv_d;
+        g[n] = (uint16_t)bf16_rne((prob - ((int)n == label ? 1.0f : 0.0f)) * inv_m);
     }
-    if (lane == 0) partial[wave] = loss;
-    __syncthreads();
-    if (threadIdx.x == 0) *p.loss = (partial[0] + partial[1] + partial[2] + partial[3]) * inv_m;
+}
+
+__global__ __launch_bounds__(64) void loss_mean(LossArgs a)
+{
+    const LossProblem &p = a.p[blockIdx.x];
+    if (threadIdx.x != 0) return;
+    float sum = 0.0f;
+    for (uint32_t r = 0; r < p.M; ++r) sum += p.row_loss[r];
+    *p.loss = sum / (float)p.M;
 }
 
 hipError_t launch_softmax_xent(const LossProblem *p, uint32_t n, hipStream_t stream, uint64_t *launches)
@@ -85,8 +95,15 @@ hipError_t launch_softmax_xent(const LossProblem *p, uint32_t n, hipStream_t str
     for (uint32_t at = 0; at < n; at += kMaxProblems) {
         LossArgs a{};
         a.n = std::min(kMaxProblems, n - at);
-        for (uint32_t i = 0; i < a.n; ++i) a.p[i] = p[at + i];
-        hipLaunchKernelGGL(softmax_xent_rows, dim3(a.n), dim3(256), 0, stream, a);
+        uint64_t blocks = 0;
+        for (uint32_t i = 0; i < a.n; ++i) {
+            a.p[i] = p[at + i];
+            blocks += (a.p[i].M + 3) / 4;
+        }
+        if (blocks == 0) continue;
+        if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(softmax_xent_rows, dim3((uint32_t)blocks), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(loss_mean, dim3(a.n), dim3(64), 0, stream, a);
         if (launches) *launches += 1;
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
