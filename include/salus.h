@@ -63,6 +63,12 @@ enum { SALUS_ACT_NONE = 0, SALUS_ACT_RELU = 1, SALUS_ACT_GELU = 2 };
 
 enum { SALUS_F32 = 0, SALUS_BF16 = 1 };
 
+/* Pool options.  SHRINK_LANES: when the job with the largest ephemeral peak leaves
+ * a lane that other jobs still use, the lane shrinks to the largest remaining
+ * peak, so that L_j = max E_i holds as an equality (Section 3.3.2); younger
+ * lanes slide up without any copy.  Off by default: Algorithm 1 never shrinks. */
+enum { SALUS_FLAG_SHRINK_LANES = 1 };
+
 /* How switch_out / switch_in cross the host link. */
 enum { SALUS_COPY_KERNEL = 0,  /* the library's own copy kernel on mapped pinned memory */
        SALUS_COPY_DMA = 1 };   /* hipMemcpyAsync (copy engine) */
@@ -73,7 +79,7 @@ typedef struct {
     int32_t  policy;       /* SALUS_POLICY_* */
     void    *stream;       /* hipStream_t for copies and compaction; NULL = default stream */
     int32_t  copy_engine;  /* SALUS_COPY_* */
-    int32_t  reserved;
+    uint32_t flags;        /* SALUS_FLAG_* */
 } salus_config;
 
 typedef struct {
@@ -133,10 +139,11 @@ typedef struct {
 } salus_stats;
 
 enum { SALUS_EV_ADMIT = 0, SALUS_EV_EVICT = 1, SALUS_EV_RESTORE = 2, SALUS_EV_LANE_NEW = 3,
-       SALUS_EV_LANE_GROW = 4, SALUS_EV_LANE_DEL = 5, SALUS_EV_LANE_MOVED = 6, SALUS_EV_COMPACT = 7 };
+       SALUS_EV_LANE_GROW = 4, SALUS_EV_LANE_DEL = 5, SALUS_EV_LANE_MOVED = 6, SALUS_EV_COMPACT = 7,
+       SALUS_EV_LANE_SHRINK = 8 };
 
 /* kind ADMIT: a = job, b = lane | EVICT: a = job, b = bytes | RESTORE: a = job,
- * b = new persistent offset | LANE_NEW / LANE_GROW: a = lane, b = size |
+ * b = new persistent offset | LANE_NEW / LANE_GROW / LANE_SHRINK: a = lane, b = size |
  * LANE_DEL: a = lane | LANE_MOVED: a = number of lanes that slid | COMPACT:
  * a = moves, b = bytes moved. */
 typedef struct { int32_t kind; int32_t pad; uint64_t a, b; } salus_event;

@@ -36,7 +36,7 @@ EINVAL, ENOMEM, ENOTRESIDENT, EBUSY, ENEVER = -1, -2, -3, -4, -5
 
 # event kinds, in the order they are appended to Pool.events
 EV_ADMIT, EV_EVICT, EV_RESTORE, EV_LANE_NEW, EV_LANE_GROW, EV_LANE_DEL, \
-    EV_LANE_MOVED, EV_COMPACT = range(8)
+    EV_LANE_MOVED, EV_COMPACT, EV_LANE_SHRINK = range(9)
 
 
 def round_up(x, a):
@@ -68,12 +68,13 @@ class Lane:
 
 
 class Pool:
-    def __init__(self, capacity, granule=256, max_lanes=0, policy=RR, mem=None):
+    def __init__(self, capacity, granule=256, max_lanes=0, policy=RR, mem=None, shrink_lanes=False):
         assert capacity > 0 and granule > 0 and capacity % granule == 0
         self.C = capacity
         self.A = granule
         self.max_lanes = max_lanes  # 0 = unlimited
         self.policy = policy
+        self.shrink_lanes = shrink_lanes   # keep L_j == max E_i when a lane's largest job leaves
         self.mem = mem
         self.jobs = []              # all jobs ever created, index = job id
         self.lanes = []             # existing lanes in creation order
@@ -307,6 +308,19 @@ class Pool:
                 # auto defragmentation: metadata only, no bytes move
                 self.stats['lanes_moved'] += behind
                 self.events.append((EV_LANE_MOVED, behind, 0))
+        elif self.shrink_lanes:
+            # Section 3.3.2 writes L_j = max E_i as an equality, but Algorithm 1
+            # never shrinks a lane.  Optional reading: when the job with the
+            # largest peak leaves, the lane falls back to the largest remaining
+            # peak; ephemeral memory is dead between iterations, so the lanes
+            # behind it slide up for free, exactly as after a deletion.
+            need = max(j.E for j in self.jobs
+                       if j.state in (RESIDENT, EVICTED) and j.lane == lane.id)
+            if need < lane.size:
+                lane.size = need
+                behind = sum(1 for l in self.lanes if l.id > lane.id)
+                self.stats['lanes_moved'] += behind
+                self.events.append((EV_LANE_SHRINK, lane.id, need))
         self.process_requests()
         # bring back jobs that priority admission pushed out, oldest first
         for v in self.jobs:
@@ -405,6 +419,8 @@ class Pool:
             members = [j for j in self.jobs if j.state in (RESIDENT, EVICTED) and j.lane == l.id]
             assert l.ref == len(members) and l.ref > 0
             assert l.size >= max(j.E for j in members)
+            if self.shrink_lanes:
+                assert l.size == max(j.E for j in members)     # the equality of Section 3.3.2
             assert l.size % A == 0
         # lanes: contiguous, disjoint, stacked below C
         top = C

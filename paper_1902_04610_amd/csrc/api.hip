@@ -132,7 +132,8 @@ int32_t salus_pool_create(void *base, uint64_t capacity, const salus_config *cfg
     p->ops.engine = c.copy_engine;
     p->ops.error = &p->error;
     p->granule = c.granule;
-    p->core.reset(new PoolCore(capacity, c.granule, c.max_lanes, c.policy, &p->ops));
+    p->core.reset(new PoolCore(capacity, c.granule, c.max_lanes, c.policy,
+                               (c.flags & SALUS_FLAG_SHRINK_LANES) != 0, &p->ops));
     *out = p;
     return SALUS_OK;
 }

@@ -8,8 +8,9 @@ namespace salus {
 static inline uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
 PoolCore::PoolCore(uint64_t capacity, uint64_t granule, uint32_t max_lanes, int32_t policy,
-                   DeviceOps *dev)
-    : C_(capacity), A_(granule), max_lanes_(max_lanes), policy_(policy), dev_(dev) {}
+                   bool shrink_lanes, DeviceOps *dev)
+    : C_(capacity), A_(granule), max_lanes_(max_lanes), policy_(policy),
+      shrink_lanes_(shrink_lanes), dev_(dev) {}
 
 PoolCore::~PoolCore()
 {
@@ -281,6 +282,20 @@ int32_t PoolCore::finish(int32_t id)
             if (behind) {   // younger lanes slide: bookkeeping only
                 stats.lanes_moved += behind;
                 log(SALUS_EV_LANE_MOVED, behind, 0);
+            }
+        } else if (shrink_lanes_) {
+            // Section 3.3.2 states L_j = max E_i; fall back to the largest peak
+            // still in the lane (younger lanes slide up, nothing is copied)
+            uint64_t need = 0;
+            for (const Job &m : jobs_)
+                if ((m.state == SALUS_JOB_RESIDENT || m.state == SALUS_JOB_EVICTED) &&
+                    m.lane == lanes_[i].id)
+                    need = std::max(need, m.E);
+            if (need < lanes_[i].size) {
+                sumL_ -= lanes_[i].size - need;
+                lanes_[i].size = need;
+                stats.lanes_moved += lanes_.size() - 1 - i;
+                log(SALUS_EV_LANE_SHRINK, lanes_[i].id, need);
             }
         }
         break;

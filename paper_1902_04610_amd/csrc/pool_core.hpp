@@ -51,7 +51,7 @@ struct Lane {
 class PoolCore {
 public:
     PoolCore(uint64_t capacity, uint64_t granule, uint32_t max_lanes, int32_t policy,
-             DeviceOps *dev);
+             bool shrink_lanes, DeviceOps *dev);
     ~PoolCore();
 
     int32_t arrive(uint64_t P, uint64_t E, int32_t priority, uint64_t pending, int32_t *job);
@@ -92,6 +92,7 @@ private:
     uint64_t C_, A_;
     uint32_t max_lanes_;
     int32_t policy_;
+    bool shrink_lanes_;            // keep L_j == max E_i when a lane's largest job leaves
     DeviceOps *dev_;
     std::vector<Job> jobs_;
     std::vector<Lane> lanes_;             // creation order == address order from the top

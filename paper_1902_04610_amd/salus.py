@@ -18,11 +18,12 @@ JOB_QUEUED, JOB_RESIDENT, JOB_EVICTED, JOB_DONE = 0, 1, 2, 3
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 F32, BF16 = 0, 1
 COPY_KERNEL, COPY_DMA = 0, 1
+FLAG_SHRINK_LANES = 1
 
 
 class Config(C.Structure):
     _fields_ = [("granule", C.c_uint64), ("max_lanes", C.c_uint32), ("policy", C.c_int32),
-                ("stream", C.c_void_p), ("copy_engine", C.c_int32), ("reserved", C.c_int32)]
+                ("stream", C.c_void_p), ("copy_engine", C.c_int32), ("flags", C.c_uint32)]
 
 
 class JobInfo(C.Structure):
@@ -137,9 +138,10 @@ class Pool:
     one to one and return plain Python values."""
 
     def __init__(self, base_ptr, capacity, granule=256, max_lanes=0, policy=POLICY_FAIR,
-                 stream=None, copy_engine=COPY_KERNEL):
+                 stream=None, copy_engine=COPY_KERNEL, shrink_lanes=False):
         self._lib = lib()
-        cfg = Config(granule, max_lanes, policy, stream, copy_engine, 0)
+        cfg = Config(granule, max_lanes, policy, stream, copy_engine,
+                     FLAG_SHRINK_LANES if shrink_lanes else 0)
         h = C.c_void_p()
         rc = self._lib.salus_pool_create(base_ptr, capacity, C.byref(cfg), C.byref(h))
         if rc != OK:

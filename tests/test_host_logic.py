@@ -58,10 +58,11 @@ STAT_KEYS = ("rounds", "iterations", "bytes_d2h", "bytes_h2d", "bytes_d2d", "mov
              "lanes_opened", "lanes_deleted", "lanes_moved", "evictions", "restores", "admitted")
 
 
-def drive_both(seed, steps, C, granule, max_lanes, policy, size_hi):
+def drive_both(seed, steps, C, granule, max_lanes, policy, size_hi, shrink=False):
     rnd = random.Random(seed)
-    o = op.Pool(C, granule=granule, max_lanes=max_lanes, policy=policy)
-    g = salus.Pool(None, C, granule=granule, max_lanes=max_lanes, policy=policy)
+    o = op.Pool(C, granule=granule, max_lanes=max_lanes, policy=policy, shrink_lanes=shrink)
+    g = salus.Pool(None, C, granule=granule, max_lanes=max_lanes, policy=policy,
+                   shrink_lanes=shrink)
     for step in range(steps):
         r = rnd.random()
         alive = [j.id for j in o.jobs if j.state != op.DONE]
@@ -110,6 +111,13 @@ def test_tight_pool_with_many_compactions_matches_oracle():
         drive_both(100 + seed, 400, C=16 * 1024, granule=16, max_lanes=3, policy=op.RR, size_hi=2500)
 
 
+@pytest.mark.parametrize("policy", [op.RR, op.PRIORITY, op.PACK])
+def test_lane_shrinking_matches_oracle(policy):
+    for seed in range(8):
+        drive_both(300 + seed * 5 + policy, 300, C=64 * 1024, granule=64,
+                   max_lanes=[2, 3, 6][seed % 3], policy=policy, size_hi=9000, shrink=True)
+
+
 def test_workload1_layout_through_the_library():
     MiB = 1 << 20
     g = salus.Pool(None, 4 * MiB, granule=256, policy=salus.POLICY_FAIR)
@@ -141,3 +149,64 @@ def test_error_paths_need_no_gpu():
     assert g.lane_free(j) == salus.EINVAL              # double free
     with pytest.raises(salus.SalusError):
         salus.Pool(None, 1000, granule=48)             # granule must be a power of two
+
+
+@pytest.mark.parametrize("capacity_gb", [250, 48])
+def test_workload5_full_trace_metadata_matches_oracle(capacity_gb):
+    """The whole 2000-round fragmentation trace at full sizes, metadata only:
+    admissions, queueing, lane churn, compaction plans and byte counters."""
+    from paper_1902_04610_amd import synth
+    C = capacity_gb * 10 ** 9 // 256 * 256
+    trace = synth.workload5_trace(seed=4, rounds=2000)
+    o = op.Pool(C, policy=op.RR, max_lanes=6)
+    g = salus.Pool(None, C, policy=salus.POLICY_FAIR, max_lanes=6)
+    nxt, life = 0, {}
+    for rnd in range(2000):
+        while nxt < len(trace) and trace[nxt]["arrive"] <= rnd:
+            t = trace[nxt]
+            so, jo = o.job_arrive(t["P"], t["E"], 0, 10 ** 9)
+            assert g.lane_alloc(t["P"], t["E"], 0, 10 ** 9) == (so, jo)
+            life[jo] = t["life"]
+            nxt += 1
+        for j in o.jobs:
+            if j.state == op.RESIDENT and rnd - j.admit_round >= life[j.id]:
+                assert g.lane_free(j.id) == o.job_finish(j.id) == op.OK
+        assert g.schedule_iteration() == o.schedule_iteration()
+        if o.events:
+            assert [tuple(e) for e in o.events] == g.poll_events(), rnd
+            o.events.clear()
+            o.check_invariants()
+    assert snapshot_oracle(o) == snapshot_lib(g, len(o.jobs))
+    st = g.stats()
+    assert {k: o.stats[k] for k in STAT_KEYS} == {k: st[k] for k in STAT_KEYS}
+    assert len(o.jobs) > 150 and st["lanes_opened"] > 6
+    if capacity_gb == 48:
+        assert st["compactions"] > 10 and st["bytes_d2d"] > 100 * 10 ** 9
+    else:
+        assert st["bytes_d2d"] == 0          # the literal pool is never under pressure
+    g.close()
+
+
+def test_workload4_schedule_matches_oracle_over_500_rounds():
+    GB = 10 ** 9
+    C = 23 * GB // 256 * 256
+    o = op.Pool(C, policy=op.PRIORITY)
+    g = salus.Pool(None, C, policy=salus.POLICY_PRIORITY)
+    assert g.lane_alloc(20 * GB, 2 * GB, 0, 10 ** 9) == o.job_arrive(20 * GB, 2 * GB, 0, 10 ** 9)
+    running = None
+    for rnd in range(500):
+        if rnd and rnd % 50 == 0:
+            assert g.lane_alloc(2 * GB, 2 * GB, 5, 10) == o.job_arrive(2 * GB, 2 * GB, 5, 10)
+            running = (len(o.jobs) - 1, rnd + 10)
+        if running and rnd == running[1]:
+            assert g.lane_free(running[0]) == o.job_finish(running[0]) == op.OK
+            running = None
+        so = o.schedule_iteration()
+        assert g.schedule_iteration() == so
+        # while the urgent job is resident the evicted job cannot run
+        assert [j for j, _ in so] == ([running[0]] if running else [0])
+    st = g.stats()
+    assert (st["evictions"], st["restores"]) == (9, 9) == (o.stats["evictions"], o.stats["restores"])
+    assert st["bytes_d2h"] == st["bytes_h2d"] == 9 * (20 * GB // 256 * 256)
+    assert [tuple(e) for e in o.events] == g.poll_events()
+    g.close()

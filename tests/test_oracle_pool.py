@@ -431,3 +431,73 @@ def test_pack_runs_every_lane_and_fifo_runs_one_job():
     ids = [q.job_arrive(10, 50, 0, 2)[1] for _ in range(3)]
     assert [q.schedule_iteration() for _ in range(7)] == \
         [[(0, 0)], [(0, 0)], [(1, 1)], [(1, 1)], [(2, 2)], [(2, 2)], []]
+
+
+def test_lane_shrinks_to_largest_remaining_peak_when_asked():
+    """Section 3.3.2 defines L_j = max E_i over the lane's jobs.  Hand-worked:
+    C = 10000, one lane shared by E = 1000, 3000, 2000; a younger lane of 2500."""
+    p = op.Pool(10000, granule=1, max_lanes=2, policy=op.RR, shrink_lanes=True)
+    a = p.job_arrive(500, 3000)[1]
+    b = p.job_arrive(500, 2500)[1]
+    c = p.job_arrive(500, 1000)[1]          # joins the lane with least slack that fits
+    d = p.job_arrive(500, 2000)[1]
+    la = p.jobs[a].lane
+    assert p.jobs[d].lane == p.jobs[c].lane
+    lanes0 = {l.id: (p.lane_base(l.id), l.size) for l in p.lanes}
+    assert lanes0[la] == (7000, 3000)
+    p.events.clear()
+    # the largest job of a shared lane leaves: the lane falls back to the next peak
+    shared = p.jobs[c].lane
+    big = a if shared == la else b
+    was = p.lane_by_id(shared).size
+    p.job_finish(big)
+    rest = max(p.jobs[j].E for j in (c, d))
+    assert p.lane_by_id(shared).size == rest == 2000 < was
+    assert (op.EV_LANE_SHRINK, shared, 2000) in [tuple(e) for e in p.events]
+    # lanes still tile the top of the pool, in creation order, with no gap
+    top = 10000
+    for l in p.lanes:
+        top -= l.size
+        assert p.lane_base(l.id) == top
+    assert top == p.floor()
+    p.check_invariants()
+    # without the option Algorithm 1 keeps the lane at its high-water mark
+    q = op.Pool(10000, granule=1, max_lanes=2, policy=op.RR)
+    ids = [q.job_arrive(500, e)[1] for e in (3000, 2500, 1000, 2000)]
+    q.job_finish(ids[0] if q.jobs[ids[2]].lane == q.jobs[ids[0]].lane else ids[1])
+    assert q.lane_by_id(q.jobs[ids[2]].lane).size == was
+
+
+def test_lane_shrinking_frees_room_for_a_queued_job():
+    p = op.Pool(10000, granule=1, max_lanes=1, policy=op.RR, shrink_lanes=True)
+    a = p.job_arrive(1000, 6000)[1]
+    b = p.job_arrive(1000, 1000)[1]
+    st, c = p.job_arrive(5000, 1000)          # 2000 + 5000 + 6000 > C: must wait
+    assert st == op.IS_QUEUED
+    p.job_finish(a)                            # lane 6000 -> 1000, then the queue is served
+    assert p.jobs[c].state == op.RESIDENT and p.lanes[0].size == 1000
+    p.check_invariants()
+    q = op.Pool(10000, granule=1, max_lanes=1, policy=op.RR)
+    a = q.job_arrive(1000, 6000)[1]
+    q.job_arrive(1000, 1000)
+    st, c = q.job_arrive(5000, 1000)
+    q.job_finish(a)                            # 1000 + 5000 + 6000 > C still
+    assert q.jobs[c].state == op.QUEUED
+
+
+def test_lane_shrinking_keeps_the_equality_on_random_traces():
+    import random
+    hits = 0
+    for seed in range(20):
+        rnd = random.Random(seed)
+        p = op.Pool(1 << 16, granule=64, max_lanes=3, policy=op.RR, shrink_lanes=True)
+        for _ in range(300):
+            alive = [j.id for j in p.jobs if j.state != op.DONE]
+            if rnd.random() < 0.55 or not alive:
+                p.job_arrive(rnd.randint(1, 6000), rnd.randint(1, 9000), 0, 5)
+            else:
+                p.job_finish(rnd.choice(alive))
+            p.check_invariants()               # includes L_j == max E_i for every lane
+            hits += sum(1 for e in p.events if e[0] == op.EV_LANE_SHRINK)
+            p.events.clear()
+    assert hits > 50
