@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--no-switch", action="store_true", help="skip the evict/restore/compaction figures")
     ap.add_argument("--no-training", action="store_true", help="skip the packed training-step figures")
     ap.add_argument("--hot-only", action="store_true", help="only the timed packed-iteration loop (for profiling)")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the supplemental batch-size sweep")
+    ap.add_argument("--sweep-only", action="store_true", help="only the supplemental batch-size sweep")
     ap.add_argument("--train-only", action="store_true", help="only the packed training step (for profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -60,6 +62,10 @@ def main():
     if args.train_only:
         torch.cuda.set_device(0)
         print(json.dumps(training_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
+        return
+    if args.sweep_only:
+        torch.cuda.set_device(0)
+        print(json.dumps(sweep_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
         return
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -247,6 +253,8 @@ def main():
         out["switch"] = switch_figures(torch, salus, stream)
     if not args.no_training and not args.hot_only:
         out["training"] = training_figures(torch, salus, stream)
+    if not args.no_sweep and not args.hot_only:
+        out["batch_sweep"] = sweep_figures(torch, salus, stream)
     print(json.dumps(out), flush=True)
 
 
@@ -315,6 +323,64 @@ def training_figures(torch, salus, stream, jobs=8, dims=(2048, 2048, 2048, 2048,
     log(f"[training] {res}")
     pool.close()
     return res
+
+
+def sweep_figures(torch, salus, stream, batches=(32, 64, 128, 256, 512, 1024, 2048, 4096)):
+    """Supplemental, NOT the headline workload: the same 64 resident models with
+    every model at M rows per round, M from the packing regime (weight stream
+    bound) up to 4096 rows per model (compute bound), to show where the grouped
+    kernel leaves the bandwidth roof and what share of the MFMA peak it reaches."""
+    up = lambda v: (v + 255) // 256 * 256
+    Mmax = max(batches)
+    w_sizes = [k * n * 2 for k, n in zip(DIMS[:-1], DIMS[1:])]
+    w_offs = [0, w_sizes[0], w_sizes[0] + w_sizes[1]]
+    P = sum(w_sizes)
+    x_off, y_off = 0, up(Mmax * DIMS[0] * 2)
+    h_off = y_off + up(Mmax * DIMS[-1] * 4)
+    E = up(h_off + salus.forward_work_bytes(
+        Mmax, [(k, n, 0, 0) for k, n in zip(DIMS[:-1], DIMS[1:])], salus.BF16))
+    cap = MODELS * (P + E)
+    buf = torch.empty(cap, dtype=torch.uint8, device="cuda:0")
+    pool = salus.Pool(buf.data_ptr(), cap, policy=salus.POLICY_PACK, stream=stream)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(11)
+    for m in range(MODELS):
+        st, j = pool.lane_alloc(P, E, 0, 10 ** 9)
+        assert st == salus.OK and j == m
+        q = pool.job_query(m)
+        for (k, n), off in zip(zip(DIMS[:-1], DIMS[1:]), w_offs):
+            w = (torch.randn(k, n, generator=gen, device="cuda:0") * 0.02).to(torch.bfloat16)
+            buf[q.persist_off + off:q.persist_off + off + k * n * 2].copy_(w.view(torch.uint8).reshape(-1))
+        x = torch.randn(Mmax, DIMS[0], generator=gen, device="cuda:0").to(torch.bfloat16)
+        buf[q.lane_off + x_off:q.lane_off + x_off + x.numel() * 2].copy_(x.view(torch.uint8).reshape(-1))
+    layers = [(k, n, off, act) for (k, n), off, act in
+              zip(zip(DIMS[:-1], DIMS[1:]), w_offs, (salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE))]
+    mac_per_row = sum(k * n for k, n in zip(DIMS[:-1], DIMS[1:]))
+    act_bytes_per_row = 2 * DIMS[0] + sum(2 * n for n in DIMS[1:-1]) * 2 + 4 * DIMS[-1]
+    rows = []
+    for M in batches:
+        descs, keep = salus.Pool.make_descs(
+            dict(job=m, M=M, dtype=salus.BF16, layers=layers, x_off=x_off, y_off=y_off, h_off=h_off)
+            for m in range(MODELS))
+        reps = 20 if M <= 512 else 5
+        for _ in range(2):
+            assert pool.grouped_forward(descs, MODELS, stream) == salus.OK, pool.last_error()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            assert pool.grouped_forward(descs, MODELS, stream) == salus.OK
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        tf = 2.0 * mac_per_row * M * MODELS / (ms * 1e-3) / 1e12
+        gbs = MODELS * (P + M * act_bytes_per_row) / (ms * 1e-3) / 1e9
+        rows.append({"M": M, "ms": round(ms, 4), "tflops": round(tf, 1),
+                     "pct_of_bf16_mfma_peak": round(100 * tf / MFMA_BF16_PEAK_TFLOPS, 2),
+                     "hbm_gbs": round(gbs, 1)})
+        log(f"[sweep] {rows[-1]}")
+    pool.close()
+    return {"workload": "supplemental: same 64 models, every model at M rows per round "
+                        "(forward only, 3 grouped launches)", "points": rows}
 
 
 def switch_figures(torch, salus, stream):

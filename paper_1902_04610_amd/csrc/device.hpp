@@ -49,6 +49,13 @@ constexpr uint32_t kMaskPositive = 1u << 9; // multiply Y by [aux > 0] (ReLU der
 // One launch (or several when n > kMaxProblems): Y_g = act(X_g . W_g) for all g.
 hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipStream_t stream,
                                uint64_t *launches);
+// Jobs with many rows: LDS-tiled compute-bound kernel (128 x 256 tiles).
+// tiled_shape_ok says whether a problem may go there (K % 64 == 0, N % 8 == 0),
+// tiled_tiles how many workgroups it would occupy.
+bool tiled_shape_ok(const Problem &p);
+uint64_t tiled_tiles(const Problem &p);
+hipError_t launch_grouped_bf16_tiled(const Problem *p, uint32_t n, hipStream_t stream,
+                                     uint64_t *launches);
 hipError_t launch_grouped_f32(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches);
 
 // ---- training step ------------------------------------------------------------

@@ -1,0 +1,79 @@
+// Pieces shared by the grouped dense kernels: the by-value argument block, the
+// epilogue arithmetic and the workgroup -> (job, tile) lookup.
+#pragma once
+#include "device.hpp"
+#include "wave.hpp"
+
+namespace salus {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct GroupArgs {
+    uint32_t n;
+    uint32_t pad;
+    Problem p[kMaxProblems];
+};
+
+constexpr int kGemmThreads = 256;
+constexpr int kWaves = 4;
+
+#ifndef SALUS_BF16_ATTR
+#define SALUS_BF16_ATTR
+#endif
+
+__device__ inline float activate(float z, uint32_t act)
+{
+    if (act == 1) return fmaxf(z, 0.0f);
+    if (act == 2) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
+    return z;
+}
+
+// float -> bf16 bits, round to nearest, ties to even.
+__device__ inline uint32_t bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); map
+// the hardware index to a logical one so that every XCD works on a contiguous
+// range of tiles - the tiles of one job share its activations in one L2.
+__device__ inline uint32_t xcd_remap(uint32_t b, uint32_t total)
+{
+    const uint32_t x = b & 7u, slot = b >> 3;
+    const uint32_t q = total >> 3, r = total & 7u;
+    return x * q + (x < r ? x : r) + slot;
+}
+
+struct Tile {
+    int problem;
+    uint32_t m0, n0;
+};
+
+// Which (job, row tile, column tile) this workgroup owns: lane i of every
+// wavefront holds job i's tile count; an exclusive scan gives each job's first
+// tile; a ballot finds the job whose range contains this workgroup's index.
+template <int TM, int TN>
+__device__ inline Tile find_tile(const GroupArgs &a)
+{
+    const int lane = threadIdx.x & 63;
+    const bool valid = lane < (int)a.n;
+    uint32_t row_tiles = 0, count = 0;
+    if (valid) {
+        row_tiles = (a.p[lane].M + TM - 1) / TM;
+        count = row_tiles * ((a.p[lane].N + TN - 1) / TN);
+    }
+    const uint32_t first = wave_excl_scan_u32(count, nullptr);
+    const uint32_t id = xcd_remap(blockIdx.x, gridDim.x);
+    const int g = wave_find_range(first, id, valid);
+    const uint32_t t = id - __shfl(first, g, 64);
+    const uint32_t rt = __shfl(row_tiles, g, 64);
+    Tile tile;
+    tile.problem = __builtin_amdgcn_readfirstlane(g);
+    tile.m0 = (t % rt) * TM;      // row tiles of one column tile are neighbours: they share W
+    tile.n0 = (t / rt) * TN;
+    return tile;
+}
+
+}  // namespace salus

@@ -12,81 +12,11 @@
 // sub-blocks are transposed in registers into MFMA operand order, and the four
 // wavefronts of a workgroup split K and combine their partial tiles through LDS.
 #include <algorithm>
+#include <vector>
 
-#include "device.hpp"
-#include "wave.hpp"
+#include "group.hpp"
 
 namespace salus {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
-struct GroupArgs {
-    uint32_t n;
-    uint32_t pad;
-    Problem p[kMaxProblems];
-};
-
-constexpr int kGemmThreads = 256;
-constexpr int kWaves = 4;
-
-#ifndef SALUS_BF16_ATTR
-#define SALUS_BF16_ATTR
-#endif
-
-__device__ inline float activate(float z, uint32_t act)
-{
-    if (act == 1) return fmaxf(z, 0.0f);
-    if (act == 2) return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
-    return z;
-}
-
-// float -> bf16 bits, round to nearest, ties to even.
-__device__ inline uint32_t bf16_bits(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-
-// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); map
-// the hardware index to a logical one so that every XCD works on a contiguous
-// range of tiles - the tiles of one job share its activations in one L2.
-__device__ inline uint32_t xcd_remap(uint32_t b, uint32_t total)
-{
-    const uint32_t x = b & 7u, slot = b >> 3;
-    const uint32_t q = total >> 3, r = total & 7u;
-    return x * q + (x < r ? x : r) + slot;
-}
-
-struct Tile {
-    int problem;
-    uint32_t m0, n0;
-};
-
-// Which (job, row tile, column tile) this workgroup owns: lane i of every
-// wavefront holds job i's tile count; an exclusive scan gives each job's first
-// tile; a ballot finds the job whose range contains this workgroup's index.
-template <int TM, int TN>
-__device__ inline Tile find_tile(const GroupArgs &a)
-{
-    const int lane = threadIdx.x & 63;
-    const bool valid = lane < (int)a.n;
-    uint32_t row_tiles = 0, count = 0;
-    if (valid) {
-        row_tiles = (a.p[lane].M + TM - 1) / TM;
-        count = row_tiles * ((a.p[lane].N + TN - 1) / TN);
-    }
-    const uint32_t first = wave_excl_scan_u32(count, nullptr);
-    const uint32_t id = xcd_remap(blockIdx.x, gridDim.x);
-    const int g = wave_find_range(first, id, valid);
-    const uint32_t t = id - __shfl(first, g, 64);
-    const uint32_t rt = __shfl(row_tiles, g, 64);
-    Tile tile;
-    tile.problem = __builtin_amdgcn_readfirstlane(g);
-    tile.m0 = (t % rt) * TM;      // row tiles of one column tile are neighbours: they share W
-    tile.n0 = (t / rt) * TN;
-    return tile;
-}
 
 // Combine the four wavefronts' partial tiles.  Accumulator register r (0..3)
 // of every 16x16 block holds row 4*(lane/16)+r, so wavefront w ends up owning
@@ -393,9 +323,31 @@ static hipError_t launch_groups(const Problem *p, uint32_t n, uint32_t tn, uint3
     return hipSuccess;
 }
 
+// Rows per job from which the LDS-tiled kernel is used: always from 128 rows; from
+// 33 rows (where the streaming kernel needs a second row tile and reads W twice)
+// if the jobs routed there fill at least two waves of workgroups on 256 CUs.
+constexpr uint32_t kTiledAlways = 128, kTiledMaybe = 33;
+constexpr uint64_t kTiledMinGrid = 512;
+
 hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipStream_t stream,
                                uint64_t *launches)
 {
+    // Jobs with many rows reuse every weight often enough to pay for LDS staging:
+    // they go to the tiled kernel, the rest of the round to the streaming kernel.
+    if (!trans_w) {
+        uint64_t grid = 0;
+        for (uint32_t i = 0; i < n; ++i)
+            if (p[i].M >= kTiledMaybe && tiled_shape_ok(p[i])) grid += tiled_tiles(p[i]);
+        const uint32_t min_m = grid >= kTiledMinGrid ? kTiledMaybe : kTiledAlways;
+        std::vector<Problem> tiled, streamed;
+        for (uint32_t i = 0; i < n; ++i)
+            (p[i].M >= min_m && tiled_shape_ok(p[i]) ? tiled : streamed).push_back(p[i]);
+        if (!tiled.empty()) {
+            hipError_t e = launch_grouped_bf16_tiled(tiled.data(), (uint32_t)tiled.size(), stream, launches);
+            if (e != hipSuccess || streamed.empty()) return e;
+            return launch_grouped_bf16(streamed.data(), (uint32_t)streamed.size(), false, stream, launches);
+        }
+    }
     auto launch = [&](int mt, const GroupArgs &a, uint32_t tiles) {
         const dim3 grid(tiles), block(kGemmThreads);
         if (trans_w) {

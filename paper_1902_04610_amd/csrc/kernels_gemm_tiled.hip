@@ -1,0 +1,249 @@
+// Grouped dense layer for jobs that bring many rows (M >= 128, or more than 32
+// when the round holds enough of them to fill the chip with 128-row tiles): the
+// compute-bound counterpart of the weight-streaming kernel.  Same contract (one
+// launch runs one layer of every scheduled job, Salus paper, Section 3.3), but
+// here a weight is used by 128 rows per workgroup, so operands are staged
+// through LDS and every wavefront owns a 64 x 128 output block.
+//
+// Workgroup tile 128 x 256, k-slab 64, four wavefronts (2 x 2), v_mfma_f32_32x32x16_bf16.
+//   HBM -> registers : 16-byte loads, issued one slab ahead of the multiply
+//   registers -> LDS : X rows as they are; W blocks of 8 k x 8 n are transposed in
+//                      registers first, so that both operands sit in LDS as
+//                      [row or column][64 k-values] = 128 bytes per line
+//   LDS -> registers : one ds_read_b128 per 32x16 operand fragment
+// The 16-byte slot of k-chunk c in line r is c ^ swz(r), swz(r) = (r ^ r/8) % 8.
+// Fragment reads touch 32 consecutive lines at one k-chunk, the transposed W
+// writes touch lines 8 apart at one k-chunk, X writes fill whole lines: with
+// this swizzle each of them spreads every 8 lanes that the LDS serves together
+// over all 8 slots of the 128-byte bank row.
+#include <algorithm>
+
+#include "group.hpp"
+
+namespace salus {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kBM = 128, kBN = 256, kBK = 64;
+constexpr int kLine = kBK * 2;                 // bytes per LDS line
+
+__device__ inline uint32_t swz(uint32_t line) { return (line ^ (line >> 3)) & 7u; }
+
+// Tiles of one job in bands of 8 row tiles, column tiles inside a band: the 64
+// tiles an XCD runs at a time then share 8 slabs of X and 8 slabs of W in its L2.
+template <int BM, int BN>
+__device__ inline Tile find_tile_banded(const GroupArgs &a)
+{
+    const int lane = threadIdx.x & 63;
+    const bool valid = lane < (int)a.n;
+    uint32_t row_tiles = 0, col_tiles = 0;
+    if (valid) {
+        row_tiles = (a.p[lane].M + BM - 1) / BM;
+        col_tiles = (a.p[lane].N + BN - 1) / BN;
+    }
+    const uint32_t first = wave_excl_scan_u32(row_tiles * col_tiles, nullptr);
+    const uint32_t id = xcd_remap(blockIdx.x, gridDim.x);
+    const int g = wave_find_range(first, id, valid);
+    const uint32_t t = id - __shfl(first, g, 64);
+    const uint32_t rt = __shfl(row_tiles, g, 64), ct = __shfl(col_tiles, g, 64);
+    const uint32_t band = t / (8u * ct), local = t - band * 8u * ct;
+    const uint32_t rows = min(8u, rt - band * 8u);
+    Tile tile;
+    tile.problem = __builtin_amdgcn_readfirstlane(g);
+    tile.m0 = (band * 8u + local % rows) * BM;
+    tile.n0 = (local / rows) * BN;
+    return tile;
+}
+
+// erf by the rational approximation 7.1.26 of Abramowitz & Stegun (absolute
+// error below 1.5e-7, far inside half a bf16 step): one reciprocal, one
+// exponential and a degree-5 polynomial, no branches.
+__device__ inline float gelu_fast(float z)
+{
+    const float x = fabsf(z) * 0.70710678118654752440f;
+    const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
+    float q = fmaf(1.061405429f, t, -1.453152027f);
+    q = fmaf(q, t, 1.421413741f);
+    q = fmaf(q, t, -0.284496736f);
+    q = fmaf(q, t, 0.254829592f);
+    const float e = 1.0f - q * t * __expf(-x * x);        // erf(|z| / sqrt 2)
+    return 0.5f * z * (1.0f + copysignf(e, z));
+}
+
+template <int ACT, int FM, int FN>
+__device__ inline void store_tile(const f32x16 (&acc)[FM][FN], const Problem &p, const Tile &tile,
+                                  uint32_t wm, uint32_t wn, uint32_t fl, uint32_t fh)
+{
+    const uint32_t M = p.M, N = p.N;
+    const bool out_bf16 = (p.flags & kOutBf16) != 0, mask = (p.flags & kMaskPositive) != 0;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        const uint32_t col = tile.n0 + wn * (32u * FN) + 32u * j + fl;
+        if (col >= N) continue;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const uint32_t row0 = tile.m0 + wm * (32u * FM) + 32u * i + 4u * fh;
+            float v[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float z = acc[i][j][r];
+                v[r] = ACT == 1 ? fmaxf(z, 0.0f) : ACT == 2 ? gelu_fast(z) : z;
+            }
+            if (mask) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const uint32_t row = row0 + 8u * (r >> 2) + (r & 3);
+                    if (row >= M) continue;
+                    const uint32_t bits = ((const uint16_t *)p.aux)[(size_t)row * N + col];
+                    if ((bits & 0x8000u) || !(bits & 0x7fffu)) v[r] = 0.0f;
+                }
+            }
+            if (out_bf16) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const uint32_t row = row0 + 8u * (r >> 2) + (r & 3);
+                    if (row < M) ((uint16_t *)p.Y)[(size_t)row * N + col] = (uint16_t)bf16_bits(v[r]);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const uint32_t row = row0 + 8u * (r >> 2) + (r & 3);
+                    if (row < M) ((float *)p.Y)[(size_t)row * N + col] = v[r];
+                }
+            }
+        }
+    }
+}
+
+// Requires K % 64 == 0 and N % 8 == 0 (the launcher routes other shapes to the
+// streaming kernel).  Rows >= M and columns >= N are loaded from clamped
+// addresses and never stored.
+__global__ __launch_bounds__(256, 2) void grouped_dense_bf16_tiled(GroupArgs a)
+{
+    __shared__ __attribute__((aligned(128))) unsigned char smem[(kBM + kBN) * kLine];
+    unsigned char *As = smem, *Bs = smem + kBM * kLine;
+    const Tile tile = find_tile_banded<kBM, kBN>(a);
+    const Problem &p = a.p[tile.problem];
+    const uint32_t M = p.M, K = p.K, N = p.N;
+    const uint32_t t = threadIdx.x, lane = t & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const uint32_t wm = wave >> 1, wn = wave & 1u;
+    const uint16_t *W = (const uint16_t *)p.W;
+    const uint16_t *X = (const uint16_t *)p.X;
+
+    // ---- HBM -> registers -> LDS assignment
+    // X: thread owns k-chunk ca of rows ra, ra+32, ra+64, ra+96
+    const uint32_t ca = t & 7u, ra = t >> 3;
+    const uint16_t *xsrc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t row = tile.m0 + ra + 32u * i;
+        xsrc[i] = X + (size_t)(row < M ? row : M - 1) * K + 8u * ca;
+    }
+    const uint32_t xslot = ca ^ swz(ra);                 // line ra + 32*i: slot xslot ^ 4*(i%2)
+    // W: thread owns the 8 x 8 block (k-chunk kb, columns 8*nb .. 8*nb+7)
+    const uint32_t kb = lane >> 3, nb = (lane & 7u) + 8u * wave;
+    const uint32_t ncol = tile.n0 + 8u * nb;
+    const uint16_t *wsrc = W + (size_t)(8u * kb) * N + (ncol < N ? ncol : 0u);
+
+    u32x4 xr[4], wr[8];
+    auto load_slab = [&](uint32_t k0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xr[i] = *(const u32x4 *)(xsrc[i] + k0);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) wr[r] = *(const u32x4 *)(wsrc + (size_t)(k0 + r) * N);
+    };
+    auto store_slab = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *(u32x4 *)(As + (ra + 32 * i) * kLine + ((xslot ^ (4u * (i & 1))) << 4)) = xr[i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            u32x4 b;   // column i of the block: dword j = (k 2j, k 2j+1)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                b[j] = __builtin_amdgcn_perm(wr[2 * j + 1][i >> 1], wr[2 * j][i >> 1],
+                                             (i & 1) ? 0x07060302u : 0x05040100u);
+            const uint32_t line = 8u * nb + i;
+            *(u32x4 *)(Bs + line * kLine + ((kb ^ swz(line)) << 4)) = b;
+        }
+    };
+
+    // ---- LDS -> MFMA operands: fragment line = base + (lane % 32), k-chunk 2*ks + lane/32
+    const uint32_t fl = lane & 31u, fh = lane >> 5, fs = swz(fl);
+    const unsigned char *afrag = As + (wm * 64u + fl) * kLine;
+    const unsigned char *bfrag = Bs + (wn * 128u + fl) * kLine;
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const uint32_t slabs = K / kBK;
+    load_slab(0);
+    store_slab();
+    __syncthreads();
+    for (uint32_t s = 0; s < slabs; ++s) {
+        if (s + 1 < slabs) load_slab((s + 1) * kBK);
+#pragma unroll
+        for (uint32_t ks = 0; ks < 4; ++ks) {
+            // lines 32 apart differ in swz by 4: odd fragments use slot ^ 4
+            const uint32_t off = ((2u * ks + fh) ^ fs) << 4, off_odd = off ^ 64u;
+            bf16x8 av[2], bv[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) av[i] = *(const bf16x8 *)(afrag + 32 * i * kLine + (i & 1 ? off_odd : off));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bv[j] = *(const bf16x8 *)(bfrag + 32 * j * kLine + (j & 1 ? off_odd : off));
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();                     // every wavefront has read this slab
+        if (s + 1 < slabs) {
+            store_slab();
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: register r of a 32x32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+    const uint32_t act = p.flags & 0xffu;
+    if (act == 1) store_tile<1, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+    else if (act == 2) store_tile<2, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+    else store_tile<0, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+}
+
+
+bool tiled_shape_ok(const Problem &p) { return p.K != 0 && p.K % kBK == 0 && p.N % 8 == 0; }
+
+uint64_t tiled_tiles(const Problem &p)
+{
+    return (uint64_t)((p.M + kBM - 1) / kBM) * ((p.N + kBN - 1) / kBN);
+}
+
+hipError_t launch_grouped_bf16_tiled(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches)
+{
+    for (uint32_t at = 0; at < n; at += kMaxProblems) {
+        GroupArgs a{};
+        a.n = std::min(kMaxProblems, n - at);
+        uint64_t tiles = 0;
+        for (uint32_t i = 0; i < a.n; ++i) {
+            a.p[i] = p[at + i];
+            if (!tiled_shape_ok(a.p[i])) return hipErrorInvalidValue;
+            tiles += tiled_tiles(a.p[i]);
+        }
+        if (tiles == 0) continue;
+        if (tiles > 0x7fffffffull) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(grouped_dense_bf16_tiled, dim3((uint32_t)tiles), dim3(256), 0, stream, a);
+        if (launches) *launches += 1;
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace salus

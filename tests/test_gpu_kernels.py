@@ -155,6 +155,44 @@ def test_bf16_mixed_batch_sizes_and_depths_in_one_packed_iteration():
         assert e < TOL_BF16 and e < TOL_BF16_TIGHT, (j, e)
 
 
+@pytest.mark.parametrize("M", [128, 129, 200, 256, 300, 515])
+def test_bf16_jobs_with_many_rows_take_the_tiled_kernel(M):
+    """M >= 128 and K a multiple of 64: LDS-tiled kernel (128 x 256 tiles), so these
+    shapes cover several tiles, ragged row and column tails and one-slab K."""
+    shapes = [(64, 8, NONE), (192, 264, RELU), (128, 520, GELU), (1024, 256, NONE), (64, 1000, GELU)]
+    jobs = [dict(M=M, dims=(K, N), acts=[act]) for K, N, act in shapes]
+    jobs.append(dict(M=5, dims=(192, 264), acts=[GELU]))         # small job of the same round
+    jobs.append(dict(M=M, dims=(40, 72), acts=[RELU]))           # K not a multiple of 64: streamed
+    outs, refs, launches = run_jobs(jobs, salus.BF16)
+    assert launches == 2                                          # tiled + streaming, same layer depth
+    for o, r, j in zip(outs, refs, jobs):
+        assert np.isfinite(o).all(), j
+        assert norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
+
+
+def test_bf16_tiled_kernel_hidden_layers_round_to_bf16():
+    jobs = [dict(M=m, dims=(256, 512, 320, 264), acts=[GELU, RELU, NONE]) for m in (128, 333, 600)]
+    jobs.append(dict(M=7, dims=(256, 512, 320, 264), acts=[GELU, RELU, NONE]))
+    outs, refs, launches = run_jobs(jobs, salus.BF16)
+    assert launches == 6                                          # tiled + streaming per layer depth
+    for o, r, j in zip(outs, refs, jobs):
+        e = norm_rel_err(o, r)
+        assert np.isfinite(o).all() and e < TOL_BF16 and e < TOL_BF16_TIGHT, (j, e)
+
+
+def test_bf16_mid_sized_batches_go_tiled_when_the_round_fills_the_chip():
+    """33..127 rows: tiled only if the round's tiled jobs make up at least 512 workgroups."""
+    jobs = [dict(M=[33, 48, 64, 100][i % 4], dims=(64, 2048), acts=[[NONE, RELU, GELU][i % 3]]) for i in range(64)]
+    outs, refs, launches = run_jobs(jobs, salus.BF16)
+    assert launches == 1
+    for o, r, j in zip(outs, refs, jobs):
+        assert np.isfinite(o).all() and norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
+    outs, refs, launches = run_jobs(jobs[:8], salus.BF16)          # 64 workgroups: streamed instead
+    assert launches == 1
+    for o, r, j in zip(outs, refs, jobs):
+        assert norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
+
+
 def test_more_jobs_than_one_launch_holds():
     jobs = [dict(M=1 + (i % 5), dims=(64, 72), acts=[NONE]) for i in range(70)]
     outs, refs, launches = run_jobs(jobs, salus.BF16)
