@@ -47,6 +47,7 @@ def main():
     ap.add_argument("--hot-only", action="store_true", help="only the timed packed-iteration loop (for profiling)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the supplemental batch-size sweep")
     ap.add_argument("--sweep-only", action="store_true", help="only the supplemental batch-size sweep")
+    ap.add_argument("--overlap-only", action="store_true", help="only the overlapped-switching figures")
     ap.add_argument("--train-only", action="store_true", help="only the packed training step (for profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -62,6 +63,10 @@ def main():
     if args.train_only:
         torch.cuda.set_device(0)
         print(json.dumps(training_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
+        return
+    if args.overlap_only:
+        torch.cuda.set_device(0)
+        print(json.dumps(overlap_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
         return
     if args.sweep_only:
         torch.cuda.set_device(0)
@@ -213,7 +218,7 @@ def main():
         from oracle import dense
         dense.lib()
         cores = min(16, os.cpu_count() or 1)
-        sample_rounds = 2
+        sample_rounds = 4
         work = []
         for r in range(W_steps, W_steps + sample_rounds):
             for m in range(MODELS):
@@ -251,6 +256,7 @@ def main():
     # ---------------------------------------------------------------- switch path
     if not args.no_switch and not args.hot_only:
         out["switch"] = switch_figures(torch, salus, stream)
+        out["switch"]["overlapped"] = overlap_figures(torch, salus, stream)
     if not args.no_training and not args.hot_only:
         out["training"] = training_figures(torch, salus, stream)
     if not args.no_sweep and not args.hot_only:
@@ -381,6 +387,101 @@ def sweep_figures(torch, salus, stream, batches=(32, 64, 128, 256, 512, 1024, 20
     pool.close()
     return {"workload": "supplemental: same 64 models, every model at M rows per round "
                         "(forward only, 3 grouped launches)", "points": rows}
+
+
+def overlap_figures(torch, salus, stream, blob_gb=8, batch=MAX_BATCH):
+    """Overlapped switching: an 8 GB job leaves and comes back on a copy stream
+    while the 64 inference models keep running packed rounds on the pool's stream.
+    Reports the round time and the link rate, each alone and together."""
+    up = lambda v: (v + 255) // 256 * 256
+    w_sizes = [k * n * 2 for k, n in zip(DIMS[:-1], DIMS[1:])]
+    w_offs = [0, w_sizes[0], w_sizes[0] + w_sizes[1]]
+    P = sum(w_sizes)
+    x_off, y_off = 0, up(batch * DIMS[0] * 2)
+    h_off = y_off + up(batch * DIMS[-1] * 4)
+    E = up(h_off + salus.forward_work_bytes(
+        batch, [(k, n, 0, 0) for k, n in zip(DIMS[:-1], DIMS[1:])], salus.BF16))
+    blob = blob_gb * 10 ** 9 // 256 * 256
+    cap = MODELS * (P + E) + blob + 4096
+    buf = torch.empty(cap, dtype=torch.uint8, device="cuda:0")
+    buf[:MODELS * P].view(torch.bfloat16).normal_(0, 0.02)
+    pool = salus.Pool(buf.data_ptr(), cap, policy=salus.POLICY_PACK, stream=stream)
+    layers = [(k, n, off, act) for (k, n), off, act in
+              zip(zip(DIMS[:-1], DIMS[1:]), w_offs, (salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE))]
+    for m in range(MODELS):
+        st, j = pool.lane_alloc(P, E, 0, 10 ** 9)
+        assert st == salus.OK and j == m
+        q = pool.job_query(m)
+        buf[q.lane_off:q.lane_off + batch * DIMS[0] * 2].view(torch.bfloat16).normal_(0, 1)
+    st, bj = pool.lane_alloc(blob, 4096, 0, 0)
+    assert st == salus.OK
+    salus.fill_pattern(buf.data_ptr() + pool.job_query(bj).persist_off, blob, 77, stream)
+    descs, keep = salus.Pool.make_descs(
+        dict(job=m, M=batch, dtype=salus.BF16, layers=layers, x_off=x_off, y_off=y_off, h_off=h_off)
+        for m in range(MODELS))
+    slots = (salus.Slot * (MODELS + 1))()
+    copy_stream = torch.cuda.Stream()
+    cs = copy_stream.cuda_stream
+
+    def one_round():
+        assert pool.schedule_into(slots, MODELS + 1) == MODELS
+        assert pool.grouped_forward(descs, MODELS, stream) == salus.OK
+
+    def rounds_alone(n=200):
+        for _ in range(20):
+            one_round()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            one_round()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    def transfer(begin, end, with_rounds):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        assert begin() == salus.OK
+        n = 0
+        if with_rounds:
+            while end(False) == salus.EBUSY:
+                for _ in range(8):
+                    one_round()
+                n += 8
+                torch.cuda.current_stream().synchronize()     # keep the host at most 8 rounds ahead
+            dt = time.perf_counter() - t0
+        else:
+            assert end(True) == salus.OK
+            dt = time.perf_counter() - t0
+        torch.cuda.synchronize()
+        return dt, n
+
+    out_b = lambda: pool.switch_out_begin(bj, cs)
+    out_e = lambda w: pool.switch_out_end(bj, w)
+    in_b = lambda: pool.switch_in_begin(bj, cs)
+    in_e = lambda w: pool.switch_in_end(bj, w)
+    transfer(out_b, out_e, False)                  # first eviction allocates the pinned buffer: untimed
+    transfer(in_b, in_e, False)
+    alone = rounds_alone()
+    t_out, _ = transfer(out_b, out_e, False)
+    t_in, _ = transfer(in_b, in_e, False)
+    t_out_ov, n_out = transfer(out_b, out_e, True)
+    t_in_ov, n_in = transfer(in_b, in_e, True)
+    scratch = torch.zeros(8, dtype=torch.uint8, device="cuda:0")
+    bad = salus.check_pattern(buf.data_ptr() + pool.job_query(bj).persist_off, blob, 77,
+                              scratch.data_ptr(), stream)
+    res = {"workload": f"{blob_gb} GB job switched out and in on a copy stream; 64 models at batch {batch} "
+                       "run packed rounds meanwhile",
+           "round_ms_alone": round(alone * 1e3, 4),
+           "round_ms_during_evict": round(t_out_ov / max(n_out, 1) * 1e3, 4),
+           "round_ms_during_restore": round(t_in_ov / max(n_in, 1) * 1e3, 4),
+           "evict_GBs_alone": round(blob / t_out / 1e9, 2), "evict_GBs_overlapped": round(blob / t_out_ov / 1e9, 2),
+           "restore_GBs_alone": round(blob / t_in / 1e9, 2),
+           "restore_GBs_overlapped": round(blob / t_in_ov / 1e9, 2),
+           "rounds_during_evict": n_out, "rounds_during_restore": n_in,
+           "bytes_wrong_after_round_trips": int(bad)}
+    log(f"[overlap] {res}")
+    pool.close()
+    return res
 
 
 def switch_figures(torch, salus, stream):

@@ -44,7 +44,7 @@ enum {
     SALUS_EINVAL = -1,         /* bad argument / bad job id / wrong job state */
     SALUS_ENOMEM = -2,         /* safety condition would be violated */
     SALUS_ENOTRESIDENT = -3,   /* job's persistent state is not on the device */
-    SALUS_EBUSY = -4,          /* two jobs of one lane in the same launch */
+    SALUS_EBUSY = -4,          /* two jobs of one lane in the same launch; job or transfer in transit */
     SALUS_ENEVER = -5,         /* P + E > C: the job could not run even alone (Section 4.2) */
     SALUS_EHIP = -6            /* the HIP runtime reported an error */
 };
@@ -87,6 +87,8 @@ typedef struct {
     int32_t  lane;         /* lane id, -1 while queued */
     int32_t  priority;
     int32_t  auto_evicted; /* 1 if priority admission evicted it (it is restored automatically) */
+    int32_t  in_transit;   /* 1 between salus_switch_*_begin and _end: resident but not runnable */
+    int32_t  reserved;
     uint64_t P, E;         /* granule-rounded sizes */
     uint64_t persist_off;  /* valid while RESIDENT; changes on compact / switch_in */
     uint64_t lane_off;     /* current base of the job's lane; changes when older lanes vanish or grow */
@@ -254,6 +256,30 @@ int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *des
 int32_t salus_switch_out(salus_pool_t *pool, int32_t job, void *pinned_or_null);
 /* EVICTED -> RESIDENT: first-fit placement (compacting if needed), then copy back. */
 int32_t salus_switch_in(salus_pool_t *pool, int32_t job);
+
+/* Overlapped switching (Section 5.1.2: a switch must not stall the other
+ * lanes): the same two transitions split into begin and end, with the bytes
+ * moved by the copy engine on `copy_stream` (a caller-owned hipStream_t other
+ * than the pool's) while later launches on the pool's stream keep running.
+ *   out_begin: job must be RESIDENT; the transfer is ordered after all work
+ *              already submitted to the pool's stream.  Until out_end the job
+ *              keeps its block and its lane, is reported in_transit, is never
+ *              scheduled, never chosen as an eviction victim, and
+ *              salus_lane_free / salus_job_write / salus_job_read / launches
+ *              naming it return SALUS_EBUSY.
+ *   out_end:   wait != 0 blocks the host until the bytes are in the host
+ *              buffer; wait == 0 returns SALUS_EBUSY (nothing changed) while
+ *              they are not.  Then the block is freed: the job is EVICTED.
+ *   in_begin:  job must be EVICTED; placement happens here exactly as in
+ *              salus_switch_in (the job is RESIDENT and in_transit), the copy
+ *              back is ordered after all work already on the pool's stream.
+ *   in_end:    as out_end; afterwards the job is runnable.
+ * A compaction that runs while transfers are in flight is ordered after them
+ * on the device.  A pool without device memory only does the bookkeeping. */
+int32_t salus_switch_out_begin(salus_pool_t *pool, int32_t job, void *pinned_or_null, void *copy_stream);
+int32_t salus_switch_out_end(salus_pool_t *pool, int32_t job, int32_t wait);
+int32_t salus_switch_in_begin(salus_pool_t *pool, int32_t job, void *copy_stream);
+int32_t salus_switch_in_end(salus_pool_t *pool, int32_t job, int32_t wait);
 
 /* Slide all live persistent blocks to the low end in address order; new offset
  * = exclusive prefix sum of the granule-rounded sizes.  Executes the moves on

@@ -56,6 +56,7 @@ class Job:
         self.off = -1               # offset of the persistent block
         self.auto_evicted = False   # evicted by priority admission, restore automatically
         self.host = None            # bytes held on the host while EVICTED
+        self.held = False           # persistent bytes in transit: resident but not runnable
         self.arrival_round = arrival_round
         self.admit_round = -1
 
@@ -254,7 +255,7 @@ class Pool:
             job = self.jobs[jid]
             action = self.find_lane(job.P, job.E)
             if action is None and self.policy == PRIORITY:
-                victims = sorted((v for v in self.resident() if v.priority < job.priority),
+                victims = sorted((v for v in self.resident() if v.priority < job.priority and not v.held),
                                  key=lambda v: (v.priority, -v.P, -v.id))
                 S = self.sum_P()
                 need = None
@@ -292,6 +293,8 @@ class Pool:
         if not (0 <= jid < len(self.jobs)) or self.jobs[jid].state == DONE:
             return EINVAL
         job = self.jobs[jid]
+        if job.held:
+            return EBUSY
         if job.state == QUEUED:
             self.Q.remove(jid)
             job.state = DONE
@@ -344,7 +347,32 @@ class Pool:
         job = self.jobs[jid]
         if job.state != RESIDENT:
             return ENOTRESIDENT
+        if job.held:
+            return EBUSY
         self.evict(job, auto=False)
+        return OK
+
+    def hold(self, jid):
+        """Overlapped switching (the transfer of one job runs while other lanes
+        keep iterating, Section 5.1.2 fast job switching): between the start and
+        the end of a transfer the job keeps its lane and its persistent block
+        but is not runnable, cannot be chosen as an eviction victim and cannot
+        finish.  The paper gives no state machine for this; this is the reading
+        taken."""
+        if not (0 <= jid < len(self.jobs)):
+            return EINVAL
+        job = self.jobs[jid]
+        if job.state != RESIDENT:
+            return ENOTRESIDENT
+        if job.held:
+            return EBUSY
+        job.held = True
+        return OK
+
+    def release(self, jid):
+        if not (0 <= jid < len(self.jobs)) or not self.jobs[jid].held:
+            return EINVAL
+        self.jobs[jid].held = False
         return OK
 
     def switch_in(self, jid):
@@ -385,7 +413,7 @@ class Pool:
         FIFO     - only the oldest runnable job of the whole pool runs."""
         def runnable(lane):
             return [j for j in self.jobs
-                    if j.state == RESIDENT and j.lane == lane.id and j.pending > 0]
+                    if j.state == RESIDENT and j.lane == lane.id and j.pending > 0 and not j.held]
         picks = []
         if self.policy == FIFO:
             cand = [j for l in self.lanes for j in runnable(l)]
@@ -429,6 +457,7 @@ class Pool:
             assert base + l.size == top
             top = base
         assert top == self.floor()
+        assert all(j.state == RESIDENT for j in self.jobs if j.held)
         # persistent blocks: disjoint, granule aligned, below the floor
         cur = 0
         for j in self.live_blocks():

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <map>
 #include <memory>
 #include <new>
 #include <string>
@@ -25,6 +26,9 @@ struct HipOps : DeviceOps {
     int engine = SALUS_COPY_KERNEL;
     std::string *error = nullptr;
     uint64_t copy_launches = 0;
+    // transfers begun and not yet ended (job id -> fence on the pool's stream, completion event)
+    struct Transfer { hipEvent_t fence, done; };
+    std::map<int32_t, Transfer> inflight;
 
     bool present() const override { return base != nullptr; }
 
@@ -69,6 +73,12 @@ struct HipOps : DeviceOps {
     {
         std::vector<uint64_t> s(n), d(n), l(n);
         for (uint32_t i = 0; i < n; ++i) { s[i] = m[i].src; d[i] = m[i].dst; l[i] = m[i].len; }
+        // blocks with a transfer in flight may be among those that move: the moves
+        // are ordered after every such transfer
+        for (const auto &kv : inflight) {
+            hipError_t w = hipStreamWaitEvent(stream, kv.second.done, 0);
+            if (w != hipSuccess) return fail(w, "hipStreamWaitEvent");
+        }
         hipError_t e = launch_slide(base, s.data(), d.data(), l.data(), n, free_off, free_len,
                                     stream, &copy_launches);
         if (e != hipSuccess) return fail(e, "compaction launch");
@@ -141,6 +151,12 @@ int32_t salus_pool_create(void *base, uint64_t capacity, const salus_config *cfg
 int32_t salus_pool_destroy(salus_pool_t *pool)
 {
     CHECK_POOL(pool);
+    for (auto &kv : pool->ops.inflight) {     // let unfinished transfers land before their buffers go
+        (void)hipEventSynchronize(kv.second.done);
+        (void)hipEventDestroy(kv.second.fence);
+        (void)hipEventDestroy(kv.second.done);
+    }
+    pool->ops.inflight.clear();
     delete pool;
     return SALUS_OK;
 }
@@ -187,6 +203,7 @@ static int32_t job_io(salus_pool *pool, int32_t job, uint64_t off, void *host, u
     const Job *j = pool->core->job(job);
     if (!j || !host) return set_error(pool, SALUS_EINVAL, "bad job or buffer");
     if (j->state != SALUS_JOB_RESIDENT) return set_error(pool, SALUS_ENOTRESIDENT, "job is not resident");
+    if (j->held) return set_error(pool, SALUS_EBUSY, "job is in transit");
     if (off > j->P || n > j->P - off) return set_error(pool, SALUS_EINVAL, "range outside the persistent block");
     if (!pool->ops.present()) return set_error(pool, SALUS_EINVAL, "pool has no device memory");
     char *dev = pool->ops.base + j->off + off;
@@ -260,6 +277,8 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
         if (!j) return set_error(pool, SALUS_EINVAL, "descriptor names an unknown job");
         if (j->state != SALUS_JOB_RESIDENT)
             return set_error(pool, SALUS_ENOTRESIDENT, "job " + std::to_string(d.job) + " is not resident");
+        if (j->held)
+            return set_error(pool, SALUS_EBUSY, "job " + std::to_string(d.job) + " is in transit");
         if (std::find(lanes_used.begin(), lanes_used.end(), j->lane) != lanes_used.end())
             return set_error(pool, SALUS_EBUSY, "two jobs of lane " + std::to_string(j->lane) +
                                                     " in one packed iteration");
@@ -367,6 +386,8 @@ int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *des
         if (!j) return set_error(pool, SALUS_EINVAL, "descriptor names an unknown job");
         if (j->state != SALUS_JOB_RESIDENT)
             return set_error(pool, SALUS_ENOTRESIDENT, "job " + std::to_string(d.job) + " is not resident");
+        if (j->held)
+            return set_error(pool, SALUS_EBUSY, "job " + std::to_string(d.job) + " is in transit");
         if (std::find(lanes_used.begin(), lanes_used.end(), j->lane) != lanes_used.end())
             return set_error(pool, SALUS_EBUSY, "two jobs of lane " + std::to_string(j->lane) +
                                                     " in one packed iteration");
@@ -510,6 +531,81 @@ int32_t salus_switch_in(salus_pool_t *pool, int32_t job)
 {
     CHECK_POOL(pool);
     return done(pool, pool->core->switch_in(job));
+}
+
+// Starts host <-> device traffic for a held job on the caller's copy stream,
+// ordered after everything already submitted to the pool's stream.
+static int32_t start_transfer(salus_pool *pool, int32_t job, void *host, uint64_t off, uint64_t len,
+                              bool to_host, hipStream_t copy_stream)
+{
+    HipOps &ops = pool->ops;
+    if (!ops.present()) return SALUS_OK;
+    HipOps::Transfer t{};
+    hipError_t e = hipEventCreateWithFlags(&t.fence, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&t.done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventRecord(t.fence, ops.stream);
+    if (e == hipSuccess) e = hipStreamWaitEvent(copy_stream, t.fence, 0);
+    if (e == hipSuccess && len)
+        e = to_host ? hipMemcpyAsync(host, ops.base + off, len, hipMemcpyDeviceToHost, copy_stream)
+                    : hipMemcpyAsync(ops.base + off, host, len, hipMemcpyHostToDevice, copy_stream);
+    if (e == hipSuccess) e = hipEventRecord(t.done, copy_stream);
+    ops.inflight[job] = t;      // also on failure: salus_switch_*_end releases the events
+    if (e != hipSuccess) return set_error(pool, SALUS_EHIP, std::string("transfer: ") + hipGetErrorString(e));
+    return SALUS_OK;
+}
+
+// SALUS_OK when the job's transfer has completed (events released), SALUS_EBUSY
+// when it has not and wait == 0.
+static int32_t finish_transfer(salus_pool *pool, int32_t job, int32_t wait)
+{
+    HipOps &ops = pool->ops;
+    auto it = ops.inflight.find(job);
+    if (it == ops.inflight.end()) return SALUS_OK;
+    hipError_t e = wait ? hipEventSynchronize(it->second.done) : hipEventQuery(it->second.done);
+    if (e == hipErrorNotReady) return set_error(pool, SALUS_EBUSY, "transfer still in flight");
+    (void)hipEventDestroy(it->second.fence);
+    (void)hipEventDestroy(it->second.done);
+    ops.inflight.erase(it);
+    if (e != hipSuccess) return set_error(pool, SALUS_EHIP, std::string("transfer: ") + hipGetErrorString(e));
+    return SALUS_OK;
+}
+
+int32_t salus_switch_out_begin(salus_pool_t *pool, int32_t job, void *pinned_or_null, void *copy_stream)
+{
+    CHECK_POOL(pool);
+    void *host = nullptr;
+    uint64_t off = 0, len = 0;
+    if (int32_t rc = pool->core->begin_out(job, pinned_or_null, &host, &off, &len)) return done(pool, rc);
+    return start_transfer(pool, job, host, off, len, true, (hipStream_t)copy_stream);
+}
+
+int32_t salus_switch_out_end(salus_pool_t *pool, int32_t job, int32_t wait)
+{
+    CHECK_POOL(pool);
+    const Job *j = pool->core->job(job);
+    if (!j || !j->held || !j->leaving)
+        return set_error(pool, SALUS_EINVAL, "no device-to-host transfer was begun for this job");
+    if (int32_t rc = finish_transfer(pool, job, wait)) return rc;
+    return done(pool, pool->core->end_out(job));
+}
+
+int32_t salus_switch_in_begin(salus_pool_t *pool, int32_t job, void *copy_stream)
+{
+    CHECK_POOL(pool);
+    void *host = nullptr;
+    uint64_t off = 0, len = 0;
+    if (int32_t rc = pool->core->begin_in(job, &host, &off, &len)) return done(pool, rc);
+    return start_transfer(pool, job, host, off, len, false, (hipStream_t)copy_stream);
+}
+
+int32_t salus_switch_in_end(salus_pool_t *pool, int32_t job, int32_t wait)
+{
+    CHECK_POOL(pool);
+    const Job *j = pool->core->job(job);
+    if (!j || !j->held || j->leaving)
+        return set_error(pool, SALUS_EINVAL, "no host-to-device transfer was begun for this job");
+    if (int32_t rc = finish_transfer(pool, job, wait)) return rc;
+    return done(pool, pool->core->end_in(job));
 }
 
 int32_t salus_compact(salus_pool_t *pool, salus_move *plan_out, uint32_t cap, uint32_t *n_moves)

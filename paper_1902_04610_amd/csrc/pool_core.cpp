@@ -169,18 +169,24 @@ int PoolCore::admit(Job &j, Choice c)
     return SALUS_OK;
 }
 
-int PoolCore::evict(Job &j, bool automatic, void *pinned)
+int PoolCore::host_buffer(Job &j, void *pinned)
 {
-    if (dev_->present()) {
-        if (pinned) {
-            if (j.host && j.host_owned) dev_->pinned_free(j.host);
-            j.host = pinned;
-            j.host_owned = false;
-        } else if (!j.host || !j.host_owned) {
-            j.host = dev_->pinned_alloc(j.P);
-            j.host_owned = true;
-            if (!j.host) { error = "pinned host allocation failed"; return SALUS_EHIP; }
-        }
+    if (pinned) {
+        if (j.host && j.host_owned) dev_->pinned_free(j.host);
+        j.host = pinned;
+        j.host_owned = false;
+    } else if (!j.host || !j.host_owned) {
+        j.host = dev_->pinned_alloc(j.P);
+        j.host_owned = true;
+        if (!j.host) { error = "pinned host allocation failed"; return SALUS_EHIP; }
+    }
+    return SALUS_OK;
+}
+
+int PoolCore::evict(Job &j, bool automatic, void *pinned, bool copied)
+{
+    if (dev_->present() && !copied) {
+        if (int rc = host_buffer(j, pinned)) return rc;
         if (dev_->evict(j.host, j.off, j.P)) { error = "device-to-host copy failed"; return SALUS_EHIP; }
     }
     blocks_.erase(j.off);
@@ -205,7 +211,8 @@ void PoolCore::process_requests()
             // largest persistent state, then youngest
             std::vector<int32_t> victims;
             for (const Job &v : jobs_)
-                if (v.state == SALUS_JOB_RESIDENT && v.priority < j.priority) victims.push_back(v.id);
+                if (v.state == SALUS_JOB_RESIDENT && v.priority < j.priority && !v.held)
+                    victims.push_back(v.id);
             std::sort(victims.begin(), victims.end(), [&](int32_t a, int32_t b) {
                 const Job &x = jobs_[a], &y = jobs_[b];
                 if (x.priority != y.priority) return x.priority < y.priority;
@@ -259,6 +266,7 @@ int32_t PoolCore::finish(int32_t id)
         return SALUS_EINVAL;
     }
     Job &j = jobs_[id];
+    if (j.held) { error = "job is in transit"; return SALUS_EBUSY; }
     if (j.state == SALUS_JOB_QUEUED) {
         queue_.erase(std::find(queue_.begin(), queue_.end(), id));
         j.state = SALUS_JOB_DONE;
@@ -313,10 +321,63 @@ int32_t PoolCore::switch_out(int32_t id, void *pinned)
 {
     if (id < 0 || (size_t)id >= jobs_.size()) { error = "no such job"; return SALUS_EINVAL; }
     if (jobs_[id].state != SALUS_JOB_RESIDENT) { error = "job is not resident"; return SALUS_ENOTRESIDENT; }
+    if (jobs_[id].held) { error = "job is in transit"; return SALUS_EBUSY; }
     return evict(jobs_[id], false, pinned);
 }
 
-int32_t PoolCore::switch_in(int32_t id)
+int32_t PoolCore::begin_out(int32_t id, void *pinned, void **host, uint64_t *off, uint64_t *len)
+{
+    if (id < 0 || (size_t)id >= jobs_.size()) { error = "no such job"; return SALUS_EINVAL; }
+    Job &j = jobs_[id];
+    if (j.state != SALUS_JOB_RESIDENT) { error = "job is not resident"; return SALUS_ENOTRESIDENT; }
+    if (j.held) { error = "job is in transit"; return SALUS_EBUSY; }
+    if (dev_->present())
+        if (int rc = host_buffer(j, pinned)) return rc;
+    j.held = j.leaving = true;
+    *host = j.host;
+    *off = j.off;
+    *len = j.P;
+    return SALUS_OK;
+}
+
+int32_t PoolCore::end_out(int32_t id)
+{
+    if (id < 0 || (size_t)id >= jobs_.size() || !jobs_[id].held || !jobs_[id].leaving) {
+        error = "no device-to-host transfer was begun for this job";
+        return SALUS_EINVAL;
+    }
+    Job &j = jobs_[id];
+    j.held = j.leaving = false;
+    return evict(j, false, nullptr, true);
+}
+
+int32_t PoolCore::begin_in(int32_t id, void **host, uint64_t *off, uint64_t *len)
+{
+    if (int32_t rc = switch_in_impl(id, false)) return rc;
+    Job &j = jobs_[id];
+    j.held = true;
+    j.leaving = false;
+    *host = j.host;
+    *off = j.off;
+    *len = j.P;
+    return SALUS_OK;
+}
+
+int32_t PoolCore::end_in(int32_t id)
+{
+    if (id < 0 || (size_t)id >= jobs_.size() || !jobs_[id].held || jobs_[id].leaving) {
+        error = "no host-to-device transfer was begun for this job";
+        return SALUS_EINVAL;
+    }
+    Job &j = jobs_[id];
+    j.held = false;
+    if (!j.host_owned) j.host = nullptr;
+    return SALUS_OK;
+}
+
+int32_t PoolCore::switch_in(int32_t id) { return switch_in_impl(id, true); }
+
+int32_t PoolCore::switch_in_impl(int32_t id, bool copy_now)
 {
     if (id < 0 || (size_t)id >= jobs_.size() || jobs_[id].state != SALUS_JOB_EVICTED) {
         error = "job is not evicted";
@@ -328,11 +389,13 @@ int32_t PoolCore::switch_in(int32_t id)
     j.state = SALUS_JOB_RESIDENT;
     j.auto_evicted = false;
     sumP_ += j.P;
-    if (dev_->present() && dev_->restore(j.off, j.host, j.P)) {
-        error = "host-to-device copy failed";
-        return SALUS_EHIP;
+    if (copy_now) {
+        if (dev_->present() && dev_->restore(j.off, j.host, j.P)) {
+            error = "host-to-device copy failed";
+            return SALUS_EHIP;
+        }
+        if (!j.host_owned) j.host = nullptr;    // the caller's buffer is released; ours stays cached
     }
-    if (!j.host_owned) j.host = nullptr;    // the caller's buffer is released; ours stays cached
     stats.restores += 1;
     stats.bytes_h2d += j.P;
     log(SALUS_EV_RESTORE, j.id, j.off);
@@ -357,6 +420,8 @@ int32_t PoolCore::query(int32_t id, salus_job_info *o) const
     o->lane = j.lane;
     o->priority = j.priority;
     o->auto_evicted = j.auto_evicted;
+    o->in_transit = j.held;
+    o->reserved = 0;
     o->P = j.P;
     o->E = j.E;
     o->persist_off = j.state == SALUS_JOB_RESIDENT ? j.off : UINT64_MAX;
@@ -393,7 +458,7 @@ int32_t PoolCore::schedule(salus_slot *out, uint32_t cap, uint32_t *n)
         }
     };
     for (const Job &j : jobs_) {
-        if (j.state != SALUS_JOB_RESIDENT || j.pending == 0) continue;
+        if (j.state != SALUS_JOB_RESIDENT || j.pending == 0 || j.held) continue;
         auto it = best.find(j.lane);
         if (it == best.end()) best[j.lane] = j.id;
         else if (better(j, jobs_[it->second])) it->second = j.id;

@@ -39,6 +39,8 @@ struct Job {
     bool auto_evicted = false;
     void *host = nullptr;        // evicted bytes, or a cached pinned buffer
     bool host_owned = false;     // allocated by the library
+    bool held = false;           // persistent bytes in transit: resident, not runnable
+    bool leaving = false;        // held by begin_out (the transfer is device -> host)
     uint64_t arrival_round = 0, admit_round = UINT64_MAX;
 };
 
@@ -61,6 +63,12 @@ public:
     int32_t schedule(salus_slot *out, uint32_t cap, uint32_t *n);
     int32_t switch_out(int32_t job, void *pinned);
     int32_t switch_in(int32_t job);
+    // Overlapped switching: begin_* decides and reserves, the caller moves the
+    // bytes (host, offset, length are returned), end_* completes the bookkeeping.
+    int32_t begin_out(int32_t job, void *pinned, void **host, uint64_t *off, uint64_t *len);
+    int32_t end_out(int32_t job);
+    int32_t begin_in(int32_t job, void **host, uint64_t *off, uint64_t *len);
+    int32_t end_in(int32_t job);
     int32_t compact(std::vector<salus_move> *plan);
 
     const Job *job(int32_t id) const {
@@ -85,7 +93,9 @@ private:
     int admit(Job &j, Choice c);
     int place(Job &j, uint64_t fl);
     bool first_fit(uint64_t P, uint64_t fl, uint64_t *off) const;
-    int evict(Job &j, bool automatic, void *pinned);
+    int evict(Job &j, bool automatic, void *pinned, bool copied = false);
+    int host_buffer(Job &j, void *pinned);
+    int32_t switch_in_impl(int32_t job, bool copy_now);
     int do_compact(std::vector<salus_move> *plan);
     void log(int32_t kind, uint64_t a, uint64_t b) { events.push_back({kind, 0, a, b}); }
 

@@ -28,7 +28,8 @@ class Config(C.Structure):
 
 class JobInfo(C.Structure):
     _fields_ = [("state", C.c_int32), ("lane", C.c_int32), ("priority", C.c_int32),
-                ("auto_evicted", C.c_int32), ("P", C.c_uint64), ("E", C.c_uint64),
+                ("auto_evicted", C.c_int32), ("in_transit", C.c_int32), ("reserved", C.c_int32),
+                ("P", C.c_uint64), ("E", C.c_uint64),
                 ("persist_off", C.c_uint64), ("lane_off", C.c_uint64), ("lane_size", C.c_uint64),
                 ("pending", C.c_uint64), ("served", C.c_uint64),
                 ("arrival_round", C.c_uint64), ("admit_round", C.c_uint64)]
@@ -93,6 +94,10 @@ _PROTOS = {
     "salus_grouped_train_step": [C.c_void_p, C.POINTER(TrainDesc), C.c_uint32, C.c_void_p],
     "salus_switch_out": [C.c_void_p, C.c_int32, C.c_void_p],
     "salus_switch_in": [C.c_void_p, C.c_int32],
+    "salus_switch_out_begin": [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p],
+    "salus_switch_out_end": [C.c_void_p, C.c_int32, C.c_int32],
+    "salus_switch_in_begin": [C.c_void_p, C.c_int32, C.c_void_p],
+    "salus_switch_in_end": [C.c_void_p, C.c_int32, C.c_int32],
     "salus_compact": [C.c_void_p, C.POINTER(Move), C.c_uint32, C.POINTER(C.c_uint32)],
     "salus_get_stats": [C.c_void_p, C.POINTER(Stats)],
     "salus_poll_events": [C.c_void_p, C.POINTER(Event), C.c_uint32, C.POINTER(C.c_uint32)],
@@ -265,6 +270,18 @@ class Pool:
 
     def switch_in(self, job):
         return self._lib.salus_switch_in(self._h, job)
+
+    def switch_out_begin(self, job, copy_stream, pinned_ptr=None):
+        return self._lib.salus_switch_out_begin(self._h, job, pinned_ptr, copy_stream)
+
+    def switch_out_end(self, job, wait=True):
+        return self._lib.salus_switch_out_end(self._h, job, 1 if wait else 0)
+
+    def switch_in_begin(self, job, copy_stream):
+        return self._lib.salus_switch_in_begin(self._h, job, copy_stream)
+
+    def switch_in_end(self, job, wait=True):
+        return self._lib.salus_switch_in_end(self._h, job, 1 if wait else 0)
 
     def compact(self, cap=4096):
         plan = (Move * cap)()

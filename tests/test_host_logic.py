@@ -37,7 +37,7 @@ def snapshot_oracle(p):
                      j.off if j.state == op.RESIDENT else None,
                      p.lane_base(j.lane) if in_lane else None,
                      p.lane_by_id(j.lane).size if in_lane else 0,
-                     j.pending, j.served, int(j.auto_evicted and j.state == op.EVICTED)))
+                     j.pending, j.served, int(j.auto_evicted and j.state == op.EVICTED), int(j.held)))
     lanes = [(l.id, p.lane_base(l.id), l.size) for l in p.lanes]
     return jobs, lanes
 
@@ -50,7 +50,7 @@ def snapshot_lib(p, njobs):
         jobs.append((q.state, q.lane if q.state != salus.JOB_QUEUED else -1, q.P, q.E,
                      q.persist_off if q.state == salus.JOB_RESIDENT else None,
                      q.lane_off if in_lane else None, q.lane_size, q.pending, q.served,
-                     int(q.auto_evicted and q.state == salus.JOB_EVICTED)))
+                     int(q.auto_evicted and q.state == salus.JOB_EVICTED), q.in_transit))
     return jobs, p.lanes()
 
 
@@ -58,8 +58,12 @@ STAT_KEYS = ("rounds", "iterations", "bytes_d2h", "bytes_h2d", "bytes_d2d", "mov
              "lanes_opened", "lanes_deleted", "lanes_moved", "evictions", "restores", "admitted")
 
 
-def drive_both(seed, steps, C, granule, max_lanes, policy, size_hi, shrink=False):
+def drive_both(seed, steps, C, granule, max_lanes, policy, size_hi, shrink=False, overlapped=False):
+    """overlapped: also split switches into begin / end.  The oracle has no transfers,
+    only the rule that a job in transit is held: out_begin = hold, out_end = release +
+    switch_out, in_begin = switch_in + hold, in_end = release."""
     rnd = random.Random(seed)
+    transit = {}
     o = op.Pool(C, granule=granule, max_lanes=max_lanes, policy=policy, shrink_lanes=shrink)
     g = salus.Pool(None, C, granule=granule, max_lanes=max_lanes, policy=policy,
                    shrink_lanes=shrink)
@@ -81,6 +85,25 @@ def drive_both(seed, steps, C, granule, max_lanes, policy, size_hi, shrink=False
             jid = rnd.choice(alive)
             n = rnd.randint(0, 9)
             assert o.set_pending(jid, n) == g.job_set_pending(jid, n)
+        elif overlapped and r < 0.93:
+            jid = rnd.choice(alive + list(transit) * 2)
+            if jid in transit:
+                if transit.pop(jid) == "out":
+                    assert g.switch_out_end(jid, wait=rnd.random() < 0.5) == salus.OK
+                    assert o.release(jid) == op.OK and o.switch_out(jid) == op.OK
+                else:
+                    assert g.switch_in_end(jid) == salus.OK and o.release(jid) == op.OK
+            elif o.jobs[jid].state == op.EVICTED:
+                rc = o.switch_in(jid)
+                assert g.switch_in_begin(jid, None) == rc, (seed, step)
+                if rc == op.OK:
+                    assert o.hold(jid) == op.OK
+                    transit[jid] = "in"
+            else:
+                rc = o.hold(jid)
+                assert g.switch_out_begin(jid, None) == rc, (seed, step)
+                if rc == op.OK:
+                    transit[jid] = "out"
         elif r < 0.96:
             jid = rnd.choice(alive)
             if o.jobs[jid].state == op.EVICTED:
@@ -116,6 +139,35 @@ def test_lane_shrinking_matches_oracle(policy):
     for seed in range(8):
         drive_both(300 + seed * 5 + policy, 300, C=64 * 1024, granule=64,
                    max_lanes=[2, 3, 6][seed % 3], policy=policy, size_hi=9000, shrink=True)
+
+
+@pytest.mark.parametrize("policy", [op.RR, op.PRIORITY, op.PACK])
+def test_overlapped_switching_bookkeeping_matches_oracle(policy):
+    for seed in range(10):
+        drive_both(500 + seed * 3 + policy, 300, C=64 * 1024, granule=256,
+                   max_lanes=[0, 2, 4][seed % 3], policy=policy, size_hi=12000, overlapped=True)
+
+
+def test_overlapped_switching_error_paths():
+    g = salus.Pool(None, 1 << 20)
+    st, a = g.lane_alloc(4096, 4096, 0, 3)
+    st, b = g.lane_alloc(4096, 4096, 0, 3)
+    assert g.switch_out_end(a) == salus.EINVAL                 # nothing begun
+    assert g.switch_in_begin(a, None) == salus.EINVAL          # not evicted
+    assert g.switch_out_begin(a, None) == salus.OK
+    assert g.job_query(a).in_transit == 1 and g.job_query(a).state == salus.JOB_RESIDENT
+    assert g.switch_out_begin(a, None) == salus.EBUSY
+    assert g.switch_out(a) == salus.EBUSY and g.lane_free(a) == salus.EBUSY
+    assert g.switch_in_end(a) == salus.EINVAL                  # wrong direction
+    assert [j for j, _ in g.schedule_iteration()] == [b]       # a is not runnable
+    assert g.switch_out_end(a) == salus.OK
+    assert g.job_query(a).state == salus.JOB_EVICTED and g.job_query(a).in_transit == 0
+    assert g.switch_in_begin(a, None) == salus.OK
+    assert g.job_query(a).state == salus.JOB_RESIDENT and g.job_query(a).in_transit == 1
+    assert [j for j, _ in g.schedule_iteration()] == [b]
+    assert g.switch_in_end(a) == salus.OK
+    assert sorted(j for j, _ in g.schedule_iteration()) == [a, b]
+    g.close()
 
 
 def test_workload1_layout_through_the_library():

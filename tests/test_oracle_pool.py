@@ -501,3 +501,59 @@ def test_lane_shrinking_keeps_the_equality_on_random_traces():
             hits += sum(1 for e in p.events if e[0] == op.EV_LANE_SHRINK)
             p.events.clear()
     assert hits > 50
+
+
+# ------------------------------------------------------------------ jobs in transit
+def test_held_job_is_not_runnable_and_fair_share_catches_up():
+    p = op.Pool(1 << 20, granule=256, max_lanes=1, policy=op.RR)
+    ids = [p.job_arrive(4096, 4096, 0, 1000)[1] for _ in range(3)]
+    assert len(p.lanes) == 1
+    runs = lambda n: [p.schedule_iteration()[0][0] for _ in range(n)]
+    assert runs(6) == ids * 2                                   # 1/3 each
+    assert p.hold(ids[1]) == op.OK
+    assert runs(6) == [ids[0], ids[2]] * 3                      # 1/2 each while one is held
+    p.check_invariants()
+    assert p.release(ids[1]) == op.OK
+    assert runs(3) == [ids[1]] * 3                              # least attained service first
+    assert runs(3) == ids
+    assert [p.jobs[i].served for i in ids] == [6, 6, 6]
+
+
+def test_hold_error_codes_and_layout_is_untouched():
+    mem = np.zeros(1 << 16, np.uint8)
+    p = op.Pool(1 << 16, granule=256, mem=mem, policy=op.RR)
+    a = p.job_arrive(4096, 4096, 0, 5)[1]
+    b = p.job_arrive(8192, 4096, 0, 5)[1]
+    before = (p.jobs[a].off, p.jobs[b].off, [(l.id, l.size) for l in p.lanes])
+    assert p.hold(7) == op.EINVAL and p.release(a) == op.EINVAL
+    assert p.hold(a) == op.OK and p.hold(a) == op.EBUSY
+    assert p.job_finish(a) == op.EBUSY and p.switch_out(a) == op.EBUSY
+    assert (p.jobs[a].off, p.jobs[b].off, [(l.id, l.size) for l in p.lanes]) == before
+    assert p.switch_out(b) == op.OK and p.hold(b) == op.ENOTRESIDENT
+    assert p.release(a) == op.OK and p.job_finish(a) == op.OK
+    p.check_invariants()
+
+
+def test_priority_admission_never_evicts_a_held_job():
+    def scenario(hold_big):
+        p = op.Pool(100, granule=1, policy=op.PRIORITY, max_lanes=1)
+        big = p.job_arrive(50, 10, 0, 5)[1]
+        small = p.job_arrive(20, 10, 0, 5)[1]             # shares the lane: 70 + 10 = 80
+        if hold_big:
+            p.hold(big)
+        st, urgent = p.job_arrive(35, 10, 9, 5)           # needs 35 of the 20 that are free
+        return p, big, small, urgent, st
+    p, big, small, urgent, st = scenario(False)
+    assert st == op.OK and p.jobs[big].state == op.EVICTED and p.jobs[small].state == op.RESIDENT
+    p, big, small, urgent, st = scenario(True)            # the largest candidate is in transit
+    assert p.jobs[big].state == op.RESIDENT
+    assert st == op.OK and p.jobs[small].state == op.EVICTED      # 50 + 35 + 10 <= 100
+    p.check_invariants()
+    # and if the remaining candidates cannot make room, nothing is evicted
+    p = op.Pool(100, granule=1, policy=op.PRIORITY, max_lanes=1)
+    big = p.job_arrive(60, 10, 0, 5)[1]
+    small = p.job_arrive(10, 10, 0, 5)[1]
+    p.hold(big)
+    st, urgent = p.job_arrive(35, 10, 9, 5)               # 60 + 35 + 10 > 100 even without small
+    assert st == op.IS_QUEUED and p.jobs[small].state == op.RESIDENT
+    p.check_invariants()
