@@ -95,6 +95,8 @@ typedef struct {
     uint64_t lane_size;    /* L_j */
     uint64_t pending;      /* iterations still to run */
     uint64_t served;       /* iterations issued so far */
+    uint64_t cost;         /* duration of one iteration in the caller's time unit (default 1) */
+    uint64_t attained;     /* sum of the costs of the iterations issued so far */
     uint64_t arrival_round, admit_round;   /* admit_round = UINT64_MAX while queued */
 } salus_job_info;
 
@@ -183,6 +185,11 @@ int32_t salus_lane_free(salus_pool_t *pool, int32_t job);
 
 int32_t salus_job_query(salus_pool_t *pool, int32_t job, salus_job_info *out);
 int32_t salus_job_set_pending(salus_pool_t *pool, int32_t job, uint64_t n);
+/* Duration of one iteration of the job (measured or estimated, any unit, >= 1).
+ * FAIR equalizes the summed cost of the iterations each job was given, PRIORITY
+ * orders equal priorities by pending x cost (Section 4: attained service and
+ * remaining time are times).  Default 1: both count iterations. */
+int32_t salus_job_set_cost(salus_pool_t *pool, int32_t job, uint64_t cost);
 /* The same for count jobs at once (host arrays); stops at the first bad job id. */
 int32_t salus_set_pending_many(salus_pool_t *pool, const int32_t *jobs, const uint64_t *n,
                                uint32_t count);

@@ -50,7 +50,9 @@ class Job:
         self.E = E                  # ephemeral peak bytes, granule-rounded
         self.priority = priority    # larger number = more important
         self.pending = pending      # iterations still to run (SRTF: remaining time)
-        self.served = 0             # iterations issued so far (FAIR: attained service)
+        self.served = 0             # iterations issued so far
+        self.cost = 1               # duration of one iteration, in the caller's time unit
+        self.attained = 0           # sum of the costs of the iterations issued (FAIR: attained service)
         self.state = QUEUED
         self.lane = -1              # lane id
         self.off = -1               # offset of the persistent block
@@ -400,15 +402,27 @@ class Pool:
         self.jobs[jid].pending = n
         return OK
 
+    def set_cost(self, jid, cost):
+        """Measured or estimated duration of one iteration of the job (Section 4:
+        FAIR equalizes the service *time* jobs have received, SRTF orders by
+        remaining *time*).  With the default of 1 for every job both reduce to
+        counting iterations."""
+        if not (0 <= jid < len(self.jobs)) or self.jobs[jid].state == DONE or cost < 1:
+            return EINVAL
+        self.jobs[jid].cost = cost
+        return OK
+
     def schedule_iteration(self):
         """One scheduling round: at most one job per lane (iterations are
         serialized inside a lane and run in parallel across lanes, Section
         3.3), chosen among the lane's resident jobs that have an iteration
         pending.  Returns [(job id, lane id)] in lane creation order.
 
-        FAIR/RR  - least attained service, counted in iterations; tie: oldest job.
-        PRIORITY - highest priority, then shortest remaining, then oldest (SRTF
-                   when priorities are equal; preemption at round boundaries).
+        FAIR/RR  - least attained service (sum of the costs of the iterations
+                   issued so far); tie: oldest job.
+        PRIORITY - highest priority, then shortest remaining time (pending
+                   iterations x cost), then oldest (SRTF when priorities are
+                   equal; preemption at round boundaries).
         PACK     - every lane runs its oldest runnable job.
         FIFO     - only the oldest runnable job of the whole pool runs."""
         def runnable(lane):
@@ -425,13 +439,14 @@ class Pool:
                 if not cand:
                     continue
                 if self.policy == RR:
-                    picks.append(min(cand, key=lambda j: (j.served, j.id)))
+                    picks.append(min(cand, key=lambda j: (j.attained, j.id)))
                 elif self.policy == PRIORITY:
-                    picks.append(min(cand, key=lambda j: (-j.priority, j.pending, j.id)))
+                    picks.append(min(cand, key=lambda j: (-j.priority, j.pending * j.cost, j.id)))
                 else:
                     picks.append(min(cand, key=lambda j: j.id))
         for j in picks:
             j.served += 1
+            j.attained += j.cost
             j.pending -= 1
         self.round += 1
         self.stats['rounds'] += 1

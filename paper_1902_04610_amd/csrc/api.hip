@@ -188,6 +188,12 @@ int32_t salus_job_set_pending(salus_pool_t *pool, int32_t job, uint64_t n)
     return done(pool, pool->core->set_pending(job, n));
 }
 
+int32_t salus_job_set_cost(salus_pool_t *pool, int32_t job, uint64_t cost)
+{
+    CHECK_POOL(pool);
+    return done(pool, pool->core->set_cost(job, cost));
+}
+
 int32_t salus_set_pending_many(salus_pool_t *pool, const int32_t *jobs, const uint64_t *n,
                                uint32_t count)
 {

@@ -13,10 +13,7 @@ struct CopySeg {
     uint64_t len;        // bytes, multiple of 16; src and dst 16-byte aligned
 };
 constexpr uint32_t kMaxSeg = 64;            // segments per launch (one per wavefront lane)
-#ifndef SALUS_COPY_CHUNK_KB
-#define SALUS_COPY_CHUNK_KB 16
-#endif
-constexpr uint32_t kCopyChunk = SALUS_COPY_CHUNK_KB * 1024;  // bytes one workgroup moves per grid-stride step
+constexpr uint32_t kCopyChunk = 16 * 1024;  // bytes one workgroup moves per grid-stride step
 
 // Copies n mutually independent segments (no destination may overlap another
 // segment's source); more than kMaxSeg segments are split over launches.

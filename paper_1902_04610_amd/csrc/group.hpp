@@ -17,10 +17,6 @@ struct GroupArgs {
 constexpr int kGemmThreads = 256;
 constexpr int kWaves = 4;
 
-#ifndef SALUS_BF16_ATTR
-#define SALUS_BF16_ATTR
-#endif
-
 __device__ inline float activate(float z, uint32_t act)
 {
     if (act == 1) return fmaxf(z, 0.0f);

@@ -70,10 +70,7 @@ static uint32_t copy_grid(uint64_t chunks)
 {
     // measured on MI355X: small chunks and a grid large enough that most copies
     // need a single pass give the best read+write rate (about 5.3 TB/s)
-#ifndef SALUS_COPY_WGS_PER_CU
-#define SALUS_COPY_WGS_PER_CU 256
-#endif
-    const uint64_t cap = 256 * SALUS_COPY_WGS_PER_CU;
+    const uint64_t cap = 256 * 256;      // 256 CUs x 256 workgroups each
     return (uint32_t)std::min<uint64_t>(chunks, cap);
 }
 

@@ -70,7 +70,7 @@ constexpr int reduce_lds_floats() { return kWaves * 3 * (NACC < 16 ? NACC : 16) 
 // output column n0+8c+i are contiguous in row n0+8c+i and are loaded as they are.
 // ---------------------------------------------------------------------------
 template <int MT, bool TW>
-__global__ __launch_bounds__(kGemmThreads) SALUS_BF16_ATTR void grouped_dense_bf16(GroupArgs a)
+__global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
 {
     constexpr int TM = 16 * MT, TN = 128, NACC = MT * 8;
     __shared__ float lds[reduce_lds_floats<NACC>()];

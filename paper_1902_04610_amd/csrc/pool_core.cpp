@@ -412,6 +412,16 @@ int32_t PoolCore::set_pending(int32_t id, uint64_t n)
     return SALUS_OK;
 }
 
+int32_t PoolCore::set_cost(int32_t id, uint64_t cost)
+{
+    if (id < 0 || (size_t)id >= jobs_.size() || jobs_[id].state == SALUS_JOB_DONE || cost < 1) {
+        error = "no such live job, or a cost of zero";
+        return SALUS_EINVAL;
+    }
+    jobs_[id].cost = cost;
+    return SALUS_OK;
+}
+
 int32_t PoolCore::query(int32_t id, salus_job_info *o) const
 {
     if (id < 0 || (size_t)id >= jobs_.size() || !o) return SALUS_EINVAL;
@@ -431,6 +441,8 @@ int32_t PoolCore::query(int32_t id, salus_job_info *o) const
         o->lane_off = lane_base(j.lane, &o->lane_size);
     o->pending = j.pending;
     o->served = j.served;
+    o->cost = j.cost;
+    o->attained = j.attained;
     o->arrival_round = j.arrival_round;
     o->admit_round = j.admit_round;
     return SALUS_OK;
@@ -448,11 +460,15 @@ int32_t PoolCore::schedule(salus_slot *out, uint32_t cap, uint32_t *n)
     auto better = [&](const Job &a, const Job &b) {
         switch (policy_) {
         case SALUS_POLICY_FAIR:
-            return a.served != b.served ? a.served < b.served : a.id < b.id;
-        case SALUS_POLICY_PRIORITY:
+            return a.attained != b.attained ? a.attained < b.attained : a.id < b.id;
+        case SALUS_POLICY_PRIORITY: {
             if (a.priority != b.priority) return a.priority > b.priority;
-            if (a.pending != b.pending) return a.pending < b.pending;
+            // remaining time; 128-bit so that pending = 10^9 with large costs cannot wrap
+            const unsigned __int128 ra = (unsigned __int128)a.pending * a.cost,
+                                    rb = (unsigned __int128)b.pending * b.cost;
+            if (ra != rb) return ra < rb;
             return a.id < b.id;
+        }
         default:
             return a.id < b.id;
         }
@@ -477,6 +493,7 @@ int32_t PoolCore::schedule(salus_slot *out, uint32_t cap, uint32_t *n)
     }
     for (uint32_t i = 0; i < k; ++i) {
         jobs_[out[i].job].served += 1;
+        jobs_[out[i].job].attained += jobs_[out[i].job].cost;
         jobs_[out[i].job].pending -= 1;
     }
     *n = k;

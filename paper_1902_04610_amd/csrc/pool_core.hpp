@@ -33,6 +33,7 @@ struct Job {
     uint64_t P = 0, E = 0;
     int32_t priority = 0;
     uint64_t pending = 0, served = 0;
+    uint64_t cost = 1, attained = 0;   // iteration duration (caller's unit), sum of issued costs
     int32_t state = SALUS_JOB_QUEUED;
     int32_t lane = -1;
     uint64_t off = 0;
@@ -59,6 +60,7 @@ public:
     int32_t arrive(uint64_t P, uint64_t E, int32_t priority, uint64_t pending, int32_t *job);
     int32_t finish(int32_t job);
     int32_t set_pending(int32_t job, uint64_t n);
+    int32_t set_cost(int32_t job, uint64_t cost);
     int32_t query(int32_t job, salus_job_info *out) const;
     int32_t schedule(salus_slot *out, uint32_t cap, uint32_t *n);
     int32_t switch_out(int32_t job, void *pinned);

@@ -32,6 +32,7 @@ class JobInfo(C.Structure):
                 ("P", C.c_uint64), ("E", C.c_uint64),
                 ("persist_off", C.c_uint64), ("lane_off", C.c_uint64), ("lane_size", C.c_uint64),
                 ("pending", C.c_uint64), ("served", C.c_uint64),
+                ("cost", C.c_uint64), ("attained", C.c_uint64),
                 ("arrival_round", C.c_uint64), ("admit_round", C.c_uint64)]
 
 
@@ -84,6 +85,7 @@ _PROTOS = {
     "salus_lane_free": [C.c_void_p, C.c_int32],
     "salus_job_query": [C.c_void_p, C.c_int32, C.POINTER(JobInfo)],
     "salus_job_set_pending": [C.c_void_p, C.c_int32, C.c_uint64],
+    "salus_job_set_cost": [C.c_void_p, C.c_int32, C.c_uint64],
     "salus_set_pending_many": [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_uint64), C.c_uint32],
     "salus_job_write": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
     "salus_job_read": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
@@ -191,6 +193,9 @@ class Pool:
 
     def job_set_pending(self, job, n):
         return self._lib.salus_job_set_pending(self._h, job, n)
+
+    def job_set_cost(self, job, cost):
+        return self._lib.salus_job_set_cost(self._h, job, cost)
 
     def set_pending_many(self, jobs_arr, n_arr, count):
         """jobs_arr: ctypes int32 array, n_arr: ctypes uint64 array."""

@@ -130,3 +130,27 @@ def workload5_trace(seed=4, rounds=2000, arrival_rate=0.08, mean_life=200,
             life = int(rng.geometric(1.0 / mean_life))
             trace.append(dict(arrive=r, P=max(P, 1), E=max(E, 1), life=life))
     return trace
+
+
+def workload_trace100(seed=6, jobs=100, load=0.9):
+    """Stand-in for the 100-job training trace of Section 5.1.1 (the trace itself is
+    not available): most jobs are short and a few are long, as in the production
+    cluster the paper refers to.  All times are integer milliseconds.
+
+    Per job: arrival, persistent bytes P (lognormal, median 0.5 GB), ephemeral peak E
+    (lognormal, median 2 GB), iterations, cost = duration of one scheduling
+    quantum of the job when it has the GPU to itself, util = share of the GPU it
+    keeps busy while it runs (per mille).  Arrivals are Poisson with a rate that
+    makes the offered load `load` of one GPU used by one job at a time."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    dur_ms = np.clip(rng.lognormal(np.log(8 * 60e3), 1.3, jobs), 60e3, 4 * 3600e3)
+    cost_ms = np.clip(rng.lognormal(np.log(10e3), 0.6, jobs), 2e3, 60e3).astype(np.int64)
+    iters = np.maximum(1, np.round(dur_ms / cost_ms)).astype(np.int64)
+    P = (np.clip(rng.lognormal(np.log(0.5e9), 0.8, jobs), 5e7, 4e9) // 256 * 256).astype(np.int64)
+    E = (np.clip(rng.lognormal(np.log(2e9), 0.5, jobs), 2e8, 8e9) // 256 * 256).astype(np.int64)
+    util = rng.integers(200, 901, jobs)
+    work = int((iters * cost_ms).sum())
+    gaps = rng.exponential(work / load / jobs, jobs)
+    arrival = np.floor(np.cumsum(gaps) - gaps[0]).astype(np.int64)
+    return [dict(arrival=int(arrival[i]), P=int(P[i]), E=int(E[i]), iters=int(iters[i]),
+                 cost=int(cost_ms[i]), util=int(util[i])) for i in range(jobs)]

@@ -37,7 +37,8 @@ def snapshot_oracle(p):
                      j.off if j.state == op.RESIDENT else None,
                      p.lane_base(j.lane) if in_lane else None,
                      p.lane_by_id(j.lane).size if in_lane else 0,
-                     j.pending, j.served, int(j.auto_evicted and j.state == op.EVICTED), int(j.held)))
+                     j.pending, j.served, int(j.auto_evicted and j.state == op.EVICTED), int(j.held),
+                     j.cost, j.attained))
     lanes = [(l.id, p.lane_base(l.id), l.size) for l in p.lanes]
     return jobs, lanes
 
@@ -50,7 +51,7 @@ def snapshot_lib(p, njobs):
         jobs.append((q.state, q.lane if q.state != salus.JOB_QUEUED else -1, q.P, q.E,
                      q.persist_off if q.state == salus.JOB_RESIDENT else None,
                      q.lane_off if in_lane else None, q.lane_size, q.pending, q.served,
-                     int(q.auto_evicted and q.state == salus.JOB_EVICTED), q.in_transit))
+                     int(q.auto_evicted and q.state == salus.JOB_EVICTED), q.in_transit, q.cost, q.attained))
     return jobs, p.lanes()
 
 
@@ -81,10 +82,14 @@ def drive_both(seed, steps, C, granule, max_lanes, policy, size_hi, shrink=False
             assert o.job_finish(jid) == g.lane_free(jid), (seed, step)
         elif r < 0.85:
             assert o.schedule_iteration() == g.schedule_iteration(), (seed, step)
-        elif r < 0.90:
+        elif r < 0.88:
             jid = rnd.choice(alive)
             n = rnd.randint(0, 9)
             assert o.set_pending(jid, n) == g.job_set_pending(jid, n)
+        elif r < 0.90:
+            jid = rnd.choice(alive + [len(o.jobs) + 1])
+            c = rnd.choice([0, 1, 2, 3, 7, 10 ** 12])
+            assert o.set_cost(jid, c) == g.job_set_cost(jid, c)
         elif overlapped and r < 0.93:
             jid = rnd.choice(alive + list(transit) * 2)
             if jid in transit:

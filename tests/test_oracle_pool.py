@@ -369,11 +369,11 @@ def test_fair_share_follows_arrivals_and_departures():
     a = p.job_arrive(10, 100, 0, 10 ** 6)[1]
     assert run(6) == [a] * 6
     b = p.job_arrive(10, 100, 0, 10 ** 6)[1]
-    p.jobs[b].served = p.jobs[a].served       # a newcomer starts level with the lane (no catch-up burst)
+    p.jobs[b].attained = p.jobs[a].attained   # a newcomer starts level with the lane (no catch-up burst)
     got = run(6)
     assert got.count(a) == 3 and got.count(b) == 3
     c = p.job_arrive(10, 100, 0, 10 ** 6)[1]
-    p.jobs[c].served = p.jobs[a].served
+    p.jobs[c].attained = p.jobs[a].attained
     got = run(9)
     assert [got.count(x) for x in (a, b, c)] == [3, 3, 3]
     p.job_finish(c)
@@ -557,3 +557,40 @@ def test_priority_admission_never_evicts_a_held_job():
     st, urgent = p.job_arrive(35, 10, 9, 5)               # 60 + 35 + 10 > 100 even without small
     assert st == op.IS_QUEUED and p.jobs[small].state == op.RESIDENT
     p.check_invariants()
+
+
+# ------------------------------------------------------------------ service measured in time
+def test_fair_equalizes_attained_time_not_iteration_counts():
+    """Two jobs share a lane; one iteration of b lasts three times one of a.  Equal
+    service time means a runs three iterations for each one of b (Section 4, FAIR)."""
+    p = op.Pool(1 << 20, granule=256, max_lanes=1, policy=op.RR)
+    a = p.job_arrive(4096, 4096, 0, 1000)[1]
+    b = p.job_arrive(4096, 4096, 0, 1000)[1]
+    assert p.set_cost(b, 3) == op.OK
+    seq = [p.schedule_iteration()[0][0] for _ in range(16)]
+    # attained (a, b): (0,0) a, (1,0) b, (1,3) a a, (3,3) a, (4,3) b, (4,6) a a, (6,6) a, ...
+    assert seq == [a, b, a, a, a, b, a, a, a, b, a, a, a, b, a, a]
+    assert p.jobs[a].attained == 12 and p.jobs[b].attained == 12
+    assert p.jobs[a].served == 12 and p.jobs[b].served == 4
+    assert p.set_cost(a, 0) == op.EINVAL and p.set_cost(9, 1) == op.EINVAL
+
+
+def test_srtf_orders_by_remaining_time():
+    p = op.Pool(1 << 20, granule=256, max_lanes=1, policy=op.PRIORITY)
+    a = p.job_arrive(4096, 4096, 0, 10)[1]          # 10 iterations of 1   -> 10
+    b = p.job_arrive(4096, 4096, 0, 4)[1]           #  4 iterations of 5   -> 20
+    c = p.job_arrive(4096, 4096, 0, 6)[1]           #  6 iterations of 2   -> 12
+    p.set_cost(b, 5), p.set_cost(c, 2)
+    order = []
+    while True:
+        s = p.schedule_iteration()
+        if not s:
+            break
+        order.append(s[0][0])
+    assert order == [a] * 10 + [c] * 6 + [b] * 4    # counting iterations alone would start with b
+    # a higher priority still wins over any remaining time
+    p = op.Pool(1 << 20, granule=256, max_lanes=1, policy=op.PRIORITY)
+    a = p.job_arrive(4096, 4096, 0, 2)[1]
+    b = p.job_arrive(4096, 4096, 3, 50)[1]
+    p.set_cost(b, 100)
+    assert p.schedule_iteration()[0][0] == b
