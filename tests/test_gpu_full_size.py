@@ -251,3 +251,107 @@ def test_workload3_full_size_sampled_job():
     for k in (1, 6):
         check_step_stagewise(jobs[k], *batches[k])
     dp.close()
+
+
+# --------------------------------------------------------------------------- batch sweep (tiled kernel)
+@pytest.mark.parametrize("rows", [600, 4096])
+def test_batch_sweep_point_sampled_rows(rows):
+    """The supplemental sweep of the benchmark: 64 models at `rows` rows each go
+    through the LDS-tiled kernel.  Whole rows of sampled models are recomputed
+    by the oracle from the inputs the GPU used."""
+    DIMS, MODELS = (1024, 4096, 1024, 1024), 64
+    acts = [salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE]
+    up = lambda v: (v + 255) // 256 * 256
+    w_sizes = [k * n * 2 for k, n in zip(DIMS[:-1], DIMS[1:])]
+    w_offs = [0, w_sizes[0], w_sizes[0] + w_sizes[1]]
+    P = sum(w_sizes)
+    x_off, y_off = 0, up(rows * DIMS[0] * 2)
+    h_off = y_off + up(rows * DIMS[-1] * 4)
+    E = up(h_off + salus.forward_work_bytes(rows, [(k, n, 0, 0) for k, n in zip(DIMS[:-1], DIMS[1:])],
+                                            salus.BF16))
+    dp = big_pool(MODELS * (P + E), policy=salus.POLICY_PACK)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    layers = [(k, n, off, a) for (k, n), off, a in zip(zip(DIMS[:-1], DIMS[1:]), w_offs, acts)]
+    items = []
+    for m in range(MODELS):
+        st, j = dp.pool.lane_alloc(P, E, 0, 1)
+        assert st == salus.OK and j == m
+        q = dp.pool.job_query(m)
+        for (k, n), off in zip(zip(DIMS[:-1], DIMS[1:]), w_offs):
+            w = (torch.randn(k, n, generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
+            dp.buf[q.persist_off + off:q.persist_off + off + k * n * 2].copy_(w.view(torch.uint8).reshape(-1))
+        x = torch.randn(rows, DIMS[0], generator=gen, device="cuda").to(torch.bfloat16)
+        dp.buf[q.lane_off + x_off:q.lane_off + x_off + rows * DIMS[0] * 2].copy_(x.view(torch.uint8).reshape(-1))
+        dp.buf[q.lane_off + y_off:q.lane_off + y_off + rows * DIMS[-1] * 4].fill_(0xFF)
+        items.append(dict(job=m, M=rows, dtype=salus.BF16, layers=layers, x_off=x_off, y_off=y_off, h_off=h_off))
+    assert len(dp.pool.schedule_iteration()) == MODELS
+    descs, keep = salus.Pool.make_descs(items)
+    assert dp.pool.grouped_forward(descs, stream=dp.stream) == salus.OK
+    dp.sync()
+    assert dp.pool.stats()["gemm_launches"] == 3
+    rng = np.random.default_rng(rows)
+    worst = 0.0
+    for m in (0, MODELS - 1, int(rng.integers(1, MODELS - 1))):
+        q = dp.pool.job_query(m)
+        Y = dp.read(q.lane_off + y_off, rows * DIMS[-1] * 4, np.float32).reshape(rows, DIMS[-1])
+        assert np.isfinite(Y).all(), m                       # every element was written
+        blob = dp.read(q.persist_off, P)
+        W = [blob[o_:o_ + s].view(np.uint16).reshape(k, n)
+             for o_, s, (k, n) in zip(w_offs, w_sizes, zip(DIMS[:-1], DIMS[1:]))]
+        pick = np.unique(np.concatenate([[0, 127, 128, rows - 1], rng.integers(0, rows, 4)]))
+        X = dp.read(q.lane_off + x_off, rows * DIMS[0] * 2, np.uint16).reshape(rows, DIMS[0])[pick]
+        ref = dense.mlp_forward_bf16(np.ascontiguousarray(X), W, acts)[-1]
+        worst = max(worst, norm_rel_err(Y[pick], ref))
+    assert worst < TOL_BF16 and worst < TOL_BF16_TIGHT, worst
+    dp.close()
+
+
+# --------------------------------------------------------------------------- overlapped switching
+def test_overlapped_switch_of_20GB_while_lanes_iterate():
+    """Workload 4's 20 GB job leaves and returns on a copy stream while eight MLP
+    jobs run packed rounds; its bytes are verified on the device afterwards and the
+    MLP outputs of the last round against the oracle."""
+    from test_gpu_overlap import add_mlp_job, check_outputs, iterate
+    P_low = 20 * GB // 256 * 256
+    C = P_low + 512 * MiB
+    dp = big_pool(C, policy=salus.POLICY_PACK)
+    o = op.Pool(C, policy=op.PACK)
+    rng = np.random.default_rng(3)
+    scratch = torch.zeros(8, dtype=torch.uint8, device="cuda")
+    copy_stream = torch.cuda.Stream()
+    items, refs = zip(*[add_mlp_job(dp, o, rng, M) for M in (1, 7, 16, 32, 5, 9, 32, 2)])
+    ids = [it["job"] for it in items]
+    assert dp.pool.lane_alloc(P_low, 4096, 0, 0) == o.job_arrive(P_low, 4096, 0, 0)
+    big = len(o.jobs) - 1
+    fill(dp, o.jobs[big].off, P_low, 3)
+    rounds = {}
+    for phase in ("out", "in"):
+        if phase == "out":
+            assert dp.pool.switch_out_begin(big, copy_stream.cuda_stream) == o.hold(big) == salus.OK
+            end = dp.pool.switch_out_end
+        else:
+            fill(dp, o.jobs[ids[-1]].off + o.jobs[ids[-1]].P, P_low, 999)        # scribble over the hole
+            assert dp.pool.switch_in_begin(big, copy_stream.cuda_stream) == o.switch_in(big) == salus.OK
+            assert o.hold(big) == op.OK
+            end = dp.pool.switch_in_end
+        n = 0
+        while True:
+            rc = end(big, wait=False)
+            if rc == salus.OK:
+                break
+            assert rc == salus.EBUSY and n < 200000
+            iterate(dp, o, items, refs, ids)
+            n += 1
+            if n % 16 == 0:
+                torch.cuda.current_stream().synchronize()    # the pool's stream only, not the copy stream
+        rounds[phase] = n
+        assert o.release(big) == op.OK
+        if phase == "out":
+            assert o.switch_out(big) == op.OK
+        check_outputs(dp, items, refs)
+        same_layout(o, dp.pool)
+    same_events(o, dp.pool)
+    assert bad_words(dp, o.jobs[big].off, P_low, 3, scratch) == 0
+    assert rounds["out"] > 100 and rounds["in"] > 100          # the lanes really kept running meanwhile
+    dp.close()
