@@ -259,6 +259,8 @@ def main():
         out["switch"]["overlapped"] = overlap_figures(torch, salus, stream)
     if not args.no_training and not args.hot_only:
         out["training"] = training_figures(torch, salus, stream)
+    if not args.hot_only:
+        out["small_case_latency"] = latency_figures(torch, salus, synth, stream)
     if not args.no_sweep and not args.hot_only:
         out["batch_sweep"] = sweep_figures(torch, salus, stream)
     print(json.dumps(out), flush=True)
@@ -387,6 +389,65 @@ def sweep_figures(torch, salus, stream, batches=(32, 64, 128, 256, 512, 1024, 20
     pool.close()
     return {"workload": "supplemental: same 64 models, every model at M rows per round "
                         "(forward only, 3 grouped launches)", "points": rows}
+
+
+def latency_figures(torch, salus, synth, stream, rounds=2000):
+    """The small correctness configuration (4 jobs, two 256 x 256 float layers,
+    batch 8, two lanes, round-robin): far too small for bandwidth or flops to
+    mean anything, so it is reported as latency per scheduling round."""
+    w = synth.workload1(seed=0)
+    width, batch = w["width"], w["batch"]
+    buf = torch.zeros(w["capacity"], dtype=torch.uint8, device="cuda:0")
+    pool = salus.Pool(buf.data_ptr(), w["capacity"], granule=w["granule"], policy=salus.POLICY_FAIR,
+                      stream=stream)
+    wbytes, items = width * width * 4, []
+    for j in range(w["jobs"]):
+        st, jid = pool.lane_alloc(w["P"], w["E"], 0, 10 ** 9)
+        assert st == salus.OK
+        q = pool.job_query(jid)
+        for l in range(2):
+            t = torch.from_numpy(w["W"][j][l]).to("cuda:0")
+            buf[q.persist_off + l * wbytes:q.persist_off + (l + 1) * wbytes].copy_(t.view(torch.uint8).reshape(-1))
+        x = torch.from_numpy(w["X"][j][0]).to("cuda:0")
+        buf[q.lane_off:q.lane_off + x.numel() * 4].copy_(x.view(torch.uint8).reshape(-1))
+        items.append(dict(job=jid, M=batch, dtype=salus.F32, x_off=0, y_off=batch * width * 4,
+                          h_off=2 * batch * width * 4,
+                          layers=[(width, width, 0, salus.ACT_RELU), (width, width, wbytes, salus.ACT_NONE)]))
+    by_job = {it["job"]: it for it in items}
+    descs = {}
+    slots = (salus.Slot * 8)()
+
+    def one_round():
+        n = pool.schedule_into(slots, 8)
+        key = tuple(slots[i].job for i in range(n))
+        if key not in descs:
+            descs[key] = salus.Pool.make_descs([by_job[j] for j in key])
+        assert pool.grouped_forward(descs[key][0], n, stream) == salus.OK
+        return n
+
+    for _ in range(50):
+        one_round()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(rounds):
+        one_round()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / rounds
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    lat = []
+    for _ in range(200):                      # one round at a time: launch + execution latency
+        a.record()
+        one_round()
+        b.record()
+        b.synchronize()
+        lat.append(a.elapsed_time(b))
+    lat.sort()
+    res = {"workload": "4 jobs, two 256 x 256 float layers, batch 8, two lanes, round-robin (2 jobs per round)",
+           "us_per_round_back_to_back": round(wall * 1e6, 2),
+           "us_per_round_gpu_median": round(lat[len(lat) // 2] * 1e3, 2), "launches_per_round": 2}
+    log(f"[latency] {res}")
+    pool.close()
+    return res
 
 
 def overlap_figures(torch, salus, stream, blob_gb=8, batch=MAX_BATCH):
