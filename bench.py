@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--no-switch", action="store_true", help="skip the evict/restore/compaction figures")
     ap.add_argument("--no-training", action="store_true", help="skip the packed training-step figures")
     ap.add_argument("--hot-only", action="store_true", help="only the timed packed-iteration loop (for profiling)")
+    ap.add_argument("--poisson-only", action="store_true",
+                    help="with --hot-only: leave out the saturated rounds (for the traffic counters)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the supplemental batch-size sweep")
     ap.add_argument("--sweep-only", action="store_true", help="only the supplemental batch-size sweep")
     ap.add_argument("--overlap-only", action="store_true", help="only the overlapped-switching figures")
@@ -176,7 +178,7 @@ def main():
     log(f"pool {cap / 1e9:.2f} GB, {MODELS} models resident, {rounds} rounds planned")
     main_res = run(poisson, batches, "poisson")
     if args.hot_only:
-        sat = run(saturated, [np.full(MODELS, MAX_BATCH)] * rounds, "saturated")
+        sat = None if args.poisson_only else run(saturated, [np.full(MODELS, MAX_BATCH)] * rounds, "saturated")
         # a plain copy of known size in the same process: scale for profiler byte counters
         cal = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
         for _ in range(3):
@@ -200,7 +202,8 @@ def main():
                    "mean_batch": round(main_res["mean_batch"], 2),
                    "pct_of_bf16_mfma_peak": round(100 * main_res["tflops"] / MFMA_BF16_PEAK_TFLOPS, 3)},
         "roofline": {"bound": "hbm", "achieved": round(main_res["gbs"], 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(main_res["gbs"] / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(main_res["gbs"] / HBM_PEAK_GBS, 4),
+                     "traffic": profiled_traffic(K_steps, W_steps),
                      "kernel": "grouped_dense_bf16",
                      "avg_launch_ms": round(main_res["kernel_ms_per_launch"], 5),
                      "algorithmic_bytes_per_launch": int(main_res["bytes_per_launch"])},
@@ -389,6 +392,23 @@ def sweep_figures(torch, salus, stream, batches=(32, 64, 128, 256, 512, 1024, 20
     pool.close()
     return {"workload": "supplemental: same 64 models, every model at M rows per round "
                         "(forward only, 3 grouped launches)", "points": rows}
+
+
+def profiled_traffic(steps, warmup):
+    """HBM bytes per launch of the dominant kernel as the profiler's counters saw
+    them (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size), taken from the
+    committed summary of the same workload; None if that summary was made with
+    other --steps / --warmup than this run."""
+    path = os.path.join(ROOT, "profiles", "grouped_dense_bf16_inference_packing.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                f = dict(kv.split("=") for kv in line.split()[1:])
+                if int(f["steps"]) == steps and int(f["warmup"]) == warmup:
+                    return int(f["bytes"])
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
 
 
 def latency_figures(torch, salus, synth, stream, rounds=2000):
