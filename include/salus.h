@@ -202,9 +202,10 @@ int32_t salus_job_read(salus_pool_t *pool, int32_t job, uint64_t off, void *host
                        uint64_t nbytes);
 
 /* Sections 3.3 and 4: one scheduling round.  Picks at most one resident job
- * with pending > 0 per lane according to the policy, charges it one iteration
- * (served + 1, pending - 1) and writes the (job, lane) pairs in lane creation
- * order to out[0..*n).  cap must be >= the number of lanes. */
+ * with pending > 0 per lane according to the policy (jobs in transit are
+ * skipped), charges it one iteration (served + 1, attained + cost, pending - 1)
+ * and writes the (job, lane) pairs in lane creation order to out[0..*n).
+ * cap must be >= the number of lanes. */
 int32_t salus_schedule_iteration(salus_pool_t *pool, salus_slot *out, uint32_t cap, uint32_t *n);
 
 /* Packed iteration (Section 3.3: lanes run in parallel): the forward passes of

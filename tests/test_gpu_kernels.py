@@ -257,6 +257,10 @@ def test_forward_rejects_bad_descriptors():
     assert dp.pool.grouped_forward(mk(layers=[(64, 64, 65536 - 64, 0)])[0]) == salus.EINVAL   # weights outside P
     assert dp.pool.grouped_forward(mk(y_off=65536 - 64)[0]) == salus.EINVAL             # output outside the lane
     assert dp.pool.grouped_forward(mk(y_off=0)[0]) == salus.EINVAL                      # x and y overlap
+    assert dp.pool.grouped_forward(mk(M=0)[0]) == salus.EINVAL                          # a job without rows
+    assert dp.pool.grouped_forward(ok, n=0) == salus.OK                                 # an empty round is legal
+    launches = dp.pool.stats()["gemm_launches"]
+    assert dp.pool.grouped_forward(ok, n=0) == salus.OK and dp.pool.stats()["gemm_launches"] == launches
     assert dp.pool.switch_out(a) == salus.OK
     assert dp.pool.grouped_forward(ok) == salus.ENOTRESIDENT
     dp.close()
