@@ -115,6 +115,36 @@ __device__ inline void store_tile(const f32x16 (&acc)[FM][FN], const Problem &p,
     }
 }
 
+// Epilogue of a tile that lies wholly inside its matrix (and whose matrix is
+// below 4 GiB): no bounds tests, 32-bit byte offsets from the uniform base
+// pointer, activation and output type fixed at compile time.  This is the
+// common case; the general routine above costs about twice the instructions.
+template <int ACT, bool BF16, int FM, int FN>
+__device__ inline void store_tile_full(const f32x16 (&acc)[FM][FN], const Problem &p, const Tile &tile,
+                                       uint32_t wm, uint32_t wn, uint32_t fl, uint32_t fh)
+{
+    constexpr uint32_t esz = BF16 ? 2u : 4u;
+    const uint32_t row_bytes = p.N * esz;
+    char *Y = (char *)p.Y;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const uint32_t row0 = tile.m0 + wm * (32u * FM) + 32u * i + 4u * fh;
+            const uint32_t col = tile.n0 + wn * (32u * FN) + 32u * j + fl;
+            const uint32_t off0 = row0 * row_bytes + col * esz;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float z = acc[i][j][r];
+                const float v = ACT == 1 ? fmaxf(z, 0.0f) : ACT == 2 ? gelu_fast(z) : z;
+                const uint32_t off = off0 + (8u * (r >> 2) + (r & 3)) * row_bytes;
+                if (BF16) *(uint16_t *)(Y + off) = (uint16_t)bf16_bits(v);
+                else *(float *)(Y + off) = v;
+            }
+        }
+    }
+}
+
 // Requires K % 64 == 0 and N % 8 == 0 (the launcher routes other shapes to the
 // streaming kernel).  Rows >= M and columns >= N are loaded from clamped
 // addresses and never stored.
@@ -212,7 +242,17 @@ __global__ __launch_bounds__(256, 2) void grouped_dense_bf16_tiled(GroupArgs a)
 
     // ---- epilogue: register r of a 32x32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
     const uint32_t act = p.flags & 0xffu;
-    if (act == 1) store_tile<1, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+    const bool full = tile.m0 + kBM <= M && tile.n0 + kBN <= N && (uint64_t)M * N < (1ull << 30) &&
+                      !(p.flags & kMaskPositive);
+    if (full && (p.flags & kOutBf16)) {
+        if (act == 1) store_tile_full<1, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+        else if (act == 2) store_tile_full<2, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+        else store_tile_full<0, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+    } else if (full) {
+        if (act == 1) store_tile_full<1, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+        else if (act == 2) store_tile_full<2, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+        else store_tile_full<0, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+    } else if (act == 1) store_tile<1, 2, 4>(acc, p, tile, wm, wn, fl, fh);
     else if (act == 2) store_tile<2, 2, 4>(acc, p, tile, wm, wn, fl, fh);
     else store_tile<0, 2, 4>(acc, p, tile, wm, wn, fl, fh);
 }
