@@ -30,6 +30,7 @@ MAX_BATCH = 32
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 MiB = 1 << 20
+W_OFFS = (0, DIMS[0] * DIMS[1] * 2, DIMS[0] * DIMS[1] * 2 + DIMS[1] * DIMS[2] * 2)
 
 
 def log(*a):
@@ -50,8 +51,12 @@ def main():
     ap.add_argument("--no-sweep", action="store_true", help="skip the supplemental batch-size sweep")
     ap.add_argument("--sweep-only", action="store_true", help="only the supplemental batch-size sweep")
     ap.add_argument("--overlap-only", action="store_true", help="only the overlapped-switching figures")
+    ap.add_argument("--row-major", action="store_true",
+                    help="store the weights row-major instead of in 128-column strips")
     ap.add_argument("--train-only", action="store_true", help="only the packed training step (for profiling)")
     args = ap.parse_args()
+    global STRIP
+    STRIP = not args.row_major
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (jobs are packed inside one device); "
                  "--gpus must be 1")
@@ -102,14 +107,13 @@ def main():
         lane_off.append(q.lane_off)
         for (k, n), off in zip(zip(DIMS[:-1], DIMS[1:]), w_offs):
             w = (torch.randn(k, n, generator=gen, device=dev) * 0.02).to(torch.bfloat16)
-            buf[q.persist_off + off:q.persist_off + off + k * n * 2].copy_(w.view(torch.uint8).reshape(-1))
+            buf[q.persist_off + off:q.persist_off + off + k * n * 2].copy_(stored(w))
         x = torch.randn(MAX_BATCH, DIMS[0], generator=gen, device=dev).to(torch.bfloat16)
         buf[q.lane_off + x_off:q.lane_off + x_off + x.numel() * 2].copy_(x.view(torch.uint8).reshape(-1))
     torch.cuda.synchronize()
 
     rates, arrivals = synth.workload2_arrivals(seed=1, models=MODELS, rounds=rounds)
-    layers = [(k, n, off, act) for (k, n), off, act in
-              zip(zip(DIMS[:-1], DIMS[1:]), w_offs, (salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE))]
+    layers = layer_list(salus)
 
     def plan(batches_per_round):
         """Per round: pending flags and job descriptors, marshalled before the clock starts."""
@@ -197,7 +201,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "inference packing: 64 resident 3-layer MLPs 1024-4096-1024-1024 GELU, "
                                "bf16 weights, Poisson arrivals (rates lognormal(0,1) req/s, 4 s tick), "
-                               "batch 1-32, PACK policy, one grouped launch per layer depth",
+                               "batch 1-32, PACK policy, one grouped launch per layer depth; weights stored "
+                               + ("in 128-column strips" if STRIP else "row-major"),
                    "mean_active_models": round(main_res["mean_active"], 2),
                    "mean_batch": round(main_res["mean_batch"], 2),
                    "pct_of_bf16_mfma_peak": round(100 * main_res["tflops"] / MFMA_BF16_PEAK_TFLOPS, 3)},
@@ -231,7 +236,9 @@ def main():
         for m in sorted({m for m, _ in work}):
             q = pool.job_query(m)
             blob = buf[q.persist_off:q.persist_off + P].cpu().numpy()
-            host_w[m] = [blob[o:o + s].view(np.uint16).reshape(k, n)
+            unstrip = lambda a, k, n: (np.ascontiguousarray(a.reshape(n // 128, k, 128).transpose(1, 0, 2))
+                                       .reshape(k, n) if STRIP else a.reshape(k, n))
+            host_w[m] = [unstrip(blob[o:o + s].view(np.uint16), k, n)
                          for o, s, (k, n) in zip(w_offs, w_sizes, zip(DIMS[:-1], DIMS[1:]))]
             host_w[m].append(buf[q.lane_off:q.lane_off + MAX_BATCH * DIMS[0] * 2].cpu().numpy()
                              .view(np.uint16).reshape(MAX_BATCH, DIMS[0]))
@@ -361,11 +368,10 @@ def sweep_figures(torch, salus, stream, batches=(32, 64, 128, 256, 512, 1024, 20
         q = pool.job_query(m)
         for (k, n), off in zip(zip(DIMS[:-1], DIMS[1:]), w_offs):
             w = (torch.randn(k, n, generator=gen, device="cuda:0") * 0.02).to(torch.bfloat16)
-            buf[q.persist_off + off:q.persist_off + off + k * n * 2].copy_(w.view(torch.uint8).reshape(-1))
+            buf[q.persist_off + off:q.persist_off + off + k * n * 2].copy_(stored(w))
         x = torch.randn(Mmax, DIMS[0], generator=gen, device="cuda:0").to(torch.bfloat16)
         buf[q.lane_off + x_off:q.lane_off + x_off + x.numel() * 2].copy_(x.view(torch.uint8).reshape(-1))
-    layers = [(k, n, off, act) for (k, n), off, act in
-              zip(zip(DIMS[:-1], DIMS[1:]), w_offs, (salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE))]
+    layers = layer_list(salus)
     mac_per_row = sum(k * n for k, n in zip(DIMS[:-1], DIMS[1:]))
     act_bytes_per_row = 2 * DIMS[0] + sum(2 * n for n in DIMS[1:-1]) * 2 + 4 * DIMS[-1]
     rows = []
@@ -392,6 +398,24 @@ def sweep_figures(torch, salus, stream, batches=(32, 64, 128, 256, 512, 1024, 20
     pool.close()
     return {"workload": "supplemental: same 64 models, every model at M rows per round "
                         "(forward only, 3 grouped launches)", "points": rows}
+
+
+STRIP = True      # weights stored in 128-column strips (set False by --row-major)
+
+
+def stored(w):
+    """The bytes of a K x N bf16 weight tensor in the layout the benchmark stores:
+    the library's 128-column strips (same values, contiguous per column tile) or row-major."""
+    if STRIP:
+        k, n = w.shape
+        w = w.view(k, n // 128, 128).permute(1, 0, 2).contiguous()
+    return w.view(__import__("torch").uint8).reshape(-1)
+
+
+def layer_list(salus):
+    return [(k, n, off, act, salus.LAYOUT_STRIP128 if STRIP else salus.LAYOUT_ROWMAJOR)
+            for (k, n), off, act in zip(zip(DIMS[:-1], DIMS[1:]), W_OFFS,
+                                        (salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE))]
 
 
 def profiled_traffic(steps, warmup):
@@ -487,8 +511,7 @@ def overlap_figures(torch, salus, stream, blob_gb=8, batch=MAX_BATCH):
     buf = torch.empty(cap, dtype=torch.uint8, device="cuda:0")
     buf[:MODELS * P].view(torch.bfloat16).normal_(0, 0.02)
     pool = salus.Pool(buf.data_ptr(), cap, policy=salus.POLICY_PACK, stream=stream)
-    layers = [(k, n, off, act) for (k, n), off, act in
-              zip(zip(DIMS[:-1], DIMS[1:]), w_offs, (salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE))]
+    layers = layer_list(salus)
     for m in range(MODELS):
         st, j = pool.lane_alloc(P, E, 0, 10 ** 9)
         assert st == salus.OK and j == m

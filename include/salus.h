@@ -104,13 +104,21 @@ typedef struct { int32_t job, lane; } salus_slot;
 
 typedef struct { uint64_t src, dst, len; } salus_move;
 
-/* One layer: H_out[M x N] = act(H_in[M x K] . W[K x N]); W row-major at
- * w_off bytes inside the job's persistent block. */
+/* How a layer's K x N weights are stored.  ROWMAJOR: element (k, n) at index
+ * k * N + n.  STRIP128 (bf16 only, N a multiple of 128): columns are grouped in
+ * strips of 128 and each strip is a contiguous K x 128 block, element (k, n) at
+ * (n / 128 * K + k) * 128 + n % 128.  Same values, same results; a column tile
+ * of the kernels then streams one contiguous range of HBM instead of K separate
+ * 256-byte pieces.  salus_pack_strip128 converts on the host. */
+enum { SALUS_LAYOUT_ROWMAJOR = 0, SALUS_LAYOUT_STRIP128 = 1 };
+
+/* One layer: H_out[M x N] = act(H_in[M x K] . W[K x N]); W at w_off bytes
+ * inside the job's persistent block. */
 typedef struct {
     uint32_t K, N;
     uint64_t w_off;
     int32_t  act;          /* SALUS_ACT_* */
-    int32_t  reserved;
+    int32_t  layout;       /* SALUS_LAYOUT_* */
 } salus_layer;
 
 /* One job's forward pass in a packed iteration.  All three offsets are inside
@@ -315,6 +323,10 @@ int32_t salus_scan_u64(const uint64_t *host_in, uint32_t n, uint64_t *host_out, 
 int32_t salus_fill_pattern(void *dev, uint64_t nbytes, uint64_t seed, void *stream);
 int32_t salus_check_pattern(const void *dev, uint64_t nbytes, uint64_t seed, void *scratch,
                             uint64_t *bad, void *stream);
+/* Host helper: reorder K x N row-major 16-bit weights into SALUS_LAYOUT_STRIP128
+ * (src and dst are host pointers to K * N elements and must not overlap; N a
+ * multiple of 128).  Pure data movement. */
+int32_t salus_pack_strip128(const uint16_t *src, uint16_t *dst, uint32_t K, uint32_t N);
 /* Plain device copy with the library's copy kernel (memmove semantics when the
  * ranges overlap with dst < src). */
 int32_t salus_copy(void *dst, const void *src, uint64_t nbytes, void *stream);

@@ -301,6 +301,9 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
                 return set_error(pool, SALUS_EINVAL, "K and N must be positive multiples of 16 bytes");
             if (l && L.K != d.layers[l - 1].N) return set_error(pool, SALUS_EINVAL, "layer widths do not chain");
             if (L.act < SALUS_ACT_NONE || L.act > SALUS_ACT_GELU) return set_error(pool, SALUS_EINVAL, "bad activation");
+            if (L.layout != SALUS_LAYOUT_ROWMAJOR &&
+                (L.layout != SALUS_LAYOUT_STRIP128 || d.dtype != SALUS_BF16 || L.N % 128))
+                return set_error(pool, SALUS_EINVAL, "strip layout needs bf16 weights and N a multiple of 128");
             const uint64_t wbytes = (uint64_t)L.K * L.N * esz;
             if (L.w_off % 16 || L.w_off > j->P || wbytes > j->P - L.w_off)
                 return set_error(pool, SALUS_EINVAL, "weights outside the persistent block");
@@ -342,6 +345,7 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
                 pr.N = L.N;
                 pr.flags = (uint32_t)L.act;
                 if (bf && !last) pr.flags |= kOutBf16;
+                if (L.layout == SALUS_LAYOUT_STRIP128) pr.flags |= kStripW;
                 probs.push_back(pr);
             }
             if (probs.empty()) continue;
@@ -705,6 +709,15 @@ int32_t salus_check_pattern(const void *dev, uint64_t nbytes, uint64_t seed, voi
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     *bad = got;
     return e == hipSuccess ? SALUS_OK : SALUS_EHIP;
+}
+
+int32_t salus_pack_strip128(const uint16_t *src, uint16_t *dst, uint32_t K, uint32_t N)
+{
+    if (!src || !dst || N % 128) return SALUS_EINVAL;
+    for (uint32_t s = 0; s < N / 128; ++s)
+        for (uint32_t k = 0; k < K; ++k)
+            std::memcpy(dst + ((size_t)s * K + k) * 128, src + (size_t)k * N + (size_t)s * 128, 256);
+    return SALUS_OK;
 }
 
 int32_t salus_copy(void *dst, const void *src, uint64_t nbytes, void *stream)

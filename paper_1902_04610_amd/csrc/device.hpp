@@ -42,6 +42,7 @@ struct Problem {
 constexpr uint32_t kMaxProblems = 64;       // problems per launch (one per wavefront lane)
 constexpr uint32_t kOutBf16 = 1u << 8;      // store Y as bf16 (round to nearest even)
 constexpr uint32_t kMaskPositive = 1u << 9; // multiply Y by [aux > 0] (ReLU derivative)
+constexpr uint32_t kStripW = 1u << 10;      // W is stored in strips of 128 columns: (k, n) at (n/128 * K + k) * 128 + n % 128
 
 // One launch (or several when n > kMaxProblems): Y_g = act(X_g . W_g) for all g.
 hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipStream_t stream,

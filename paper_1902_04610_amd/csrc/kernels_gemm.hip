@@ -98,13 +98,18 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
     // how many loads may stay in flight at each use, which is what keeps the
     // next step's loads outstanding while this step is multiplied.
     const uint32_t ncol_c = col_ok ? ncol : 0u;
+    // Row-major W: row pitch N.  Strip layout: the 128 columns of this tile are one
+    // contiguous K x 128 block (pitch 128), so a wavefront's k-step is 8 KB in one piece.
+    const bool strip = !TW && (p.flags & kStripW);
+    const uint32_t wpitch = strip ? 128u : N;
+    const uint16_t *Wc = strip ? W + (size_t)tile.n0 * K + 8 * c : W + ncol_c;
     auto load = [&](int s, u32x4 (&w)[8], u32x4 (&x)[MT], bool &k_ok) {
         const uint32_t kb = 32u * (uint32_t)s + 8u * (uint32_t)g;
         k_ok = kb < K;
         const uint32_t kc = k_ok ? kb : 0u;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            const uint16_t *at = TW ? W + (size_t)(ncol_c + r) * K + kc : W + (size_t)(kc + r) * N + ncol_c;
+            const uint16_t *at = TW ? W + (size_t)(ncol_c + r) * K + kc : Wc + (size_t)(kc + r) * wpitch;
             w[r] = __builtin_nontemporal_load((const u32x4 *)at);
         }
 #pragma unroll

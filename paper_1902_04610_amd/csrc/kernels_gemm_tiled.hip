@@ -173,15 +173,18 @@ __global__ __launch_bounds__(256, 2) void grouped_dense_bf16_tiled(GroupArgs a)
     const uint32_t xslot = ca ^ swz(ra);                 // line ra + 32*i: slot xslot ^ 4*(i%2)
     // W: thread owns the 8 x 8 block (k-chunk kb, columns 8*nb .. 8*nb+7)
     const uint32_t kb = lane >> 3, nb = (lane & 7u) + 8u * wave;
-    const uint32_t ncol = tile.n0 + 8u * nb;
-    const uint16_t *wsrc = W + (size_t)(8u * kb) * N + (ncol < N ? ncol : 0u);
+    const uint32_t ncol = tile.n0 + 8u * nb, ncol_c = ncol < N ? ncol : 0u;
+    const bool strip = (p.flags & kStripW) != 0;      // W in contiguous K x 128 strips
+    const uint32_t wpitch = strip ? 128u : N;
+    const uint16_t *wsrc = strip ? W + (size_t)(ncol_c & ~127u) * K + (8u * kb) * 128u + (ncol_c & 127u)
+                                 : W + (size_t)(8u * kb) * N + ncol_c;
 
     u32x4 xr[4], wr[8];
     auto load_slab = [&](uint32_t k0) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) xr[i] = *(const u32x4 *)(xsrc[i] + k0);
 #pragma unroll
-        for (int r = 0; r < 8; ++r) wr[r] = *(const u32x4 *)(wsrc + (size_t)(k0 + r) * N);
+        for (int r = 0; r < 8; ++r) wr[r] = *(const u32x4 *)(wsrc + (size_t)(k0 + r) * wpitch);
     };
     auto store_slab = [&]() {
 #pragma unroll

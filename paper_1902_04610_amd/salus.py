@@ -18,6 +18,7 @@ JOB_QUEUED, JOB_RESIDENT, JOB_EVICTED, JOB_DONE = 0, 1, 2, 3
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
 F32, BF16 = 0, 1
 COPY_KERNEL, COPY_DMA = 0, 1
+LAYOUT_ROWMAJOR, LAYOUT_STRIP128 = 0, 1
 FLAG_SHRINK_LANES = 1
 
 
@@ -46,7 +47,7 @@ class Move(C.Structure):
 
 class Layer(C.Structure):
     _fields_ = [("K", C.c_uint32), ("N", C.c_uint32), ("w_off", C.c_uint64),
-                ("act", C.c_int32), ("reserved", C.c_int32)]
+                ("act", C.c_int32), ("layout", C.c_int32)]
 
 
 class GemmDesc(C.Structure):
@@ -111,6 +112,7 @@ _PROTOS = {
     "salus_check_pattern": [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.POINTER(C.c_uint64),
                             C.c_void_p],
     "salus_copy": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p],
+    "salus_pack_strip128": [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32],
 }
 
 _lib = None
@@ -231,13 +233,14 @@ class Pool:
     # -- packed iteration --------------------------------------------------------
     @staticmethod
     def make_descs(items):
-        """items: iterable of dicts(job, M, dtype, layers=[(K, N, w_off, act)], x_off, y_off,
-        h_off).  Returns (array, keepalive) ready for grouped_forward."""
+        """items: iterable of dicts(job, M, dtype, layers=[(K, N, w_off, act[, layout])], x_off,
+        y_off, h_off).  Returns (array, keepalive) ready for grouped_forward."""
         items = list(items)
         arr = (GemmDesc * len(items))()
         keep = []
         for i, it in enumerate(items):
-            L = (Layer * len(it["layers"]))(*[Layer(K, N, w, a, 0) for (K, N, w, a) in it["layers"]])
+            L = (Layer * len(it["layers"]))(*[Layer(t[0], t[1], t[2], t[3], t[4] if len(t) > 4 else 0)
+                                              for t in it["layers"]])
             keep.append(L)
             arr[i] = GemmDesc(it["job"], it["M"], len(it["layers"]), it["dtype"], L,
                               it["x_off"], it["y_off"], it.get("h_off", 0))
@@ -309,7 +312,7 @@ class Pool:
 
 def forward_work_bytes(M, layers, dtype):
     """layers: [(K, N, w_off, act)]"""
-    L = (Layer * len(layers))(*[Layer(K, N, w, a, 0) for (K, N, w, a) in layers])
+    L = (Layer * len(layers))(*[Layer(t[0], t[1], t[2], t[3], 0) for t in layers])
     return lib().salus_forward_work_bytes(M, L, len(layers), dtype)
 
 
@@ -341,6 +344,18 @@ def check_pattern(dev_ptr, nbytes, seed, scratch_ptr, stream=None):
     if rc != OK:
         raise SalusError(rc, "salus_check_pattern")
     return bad.value
+
+
+def pack_strip128(w):
+    """K x N uint16 (bf16 bits) numpy array, row-major -> the same values in
+    LAYOUT_STRIP128 order (a new flat array of K * N elements)."""
+    import numpy as np
+    w = np.ascontiguousarray(w, dtype=np.uint16)
+    out = np.empty(w.size, np.uint16)
+    rc = lib().salus_pack_strip128(w.ctypes.data, out.ctypes.data, w.shape[0], w.shape[1])
+    if rc != OK:
+        raise SalusError(rc, "salus_pack_strip128")
+    return out
 
 
 def copy(dst_ptr, src_ptr, nbytes, stream=None):

@@ -36,8 +36,11 @@ def bad_words(dp, off, nbytes, seed, scratch):
 
 
 # --------------------------------------------------------------------------- workload 2
-def test_workload2_full_size_sampled_outputs():
+@pytest.mark.parametrize("strip", [False, True])
+def test_workload2_full_size_sampled_outputs(strip):
+    """strip: the weights are stored in 128-column strips, as the benchmark stores them."""
     DIMS, MODELS, ROUNDS = (1024, 4096, 1024, 1024), 64, 6
+    layout = salus.LAYOUT_STRIP128 if strip else salus.LAYOUT_ROWMAJOR
     acts = [salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE]
     up = lambda v: (v + 255) // 256 * 256
     w_sizes = [k * n * 2 for k, n in zip(DIMS[:-1], DIMS[1:])]
@@ -56,10 +59,12 @@ def test_workload2_full_size_sampled_outputs():
         q = dp.pool.job_query(m)
         for (k, n), off in zip(zip(DIMS[:-1], DIMS[1:]), w_offs):
             w = (torch.randn(k, n, generator=gen, device="cuda") * 0.02).to(torch.bfloat16)
+            if strip:
+                w = w.view(k, n // 128, 128).permute(1, 0, 2).contiguous()
             dp.buf[q.persist_off + off:q.persist_off + off + k * n * 2].copy_(w.view(torch.uint8).reshape(-1))
     same_layout(o, dp.pool)
     rates, arrivals = synth.workload2_arrivals(seed=1, models=MODELS, rounds=ROUNDS)
-    layers = [(k, n, off, a) for (k, n), off, a in zip(zip(DIMS[:-1], DIMS[1:]), w_offs, acts)]
+    layers = [(k, n, off, a, layout) for (k, n), off, a in zip(zip(DIMS[:-1], DIMS[1:]), w_offs, acts)]
     waiting = np.zeros(MODELS, np.int64)
     rng = np.random.default_rng(7)
     checked, worst = 0, 0.0
@@ -95,8 +100,9 @@ def test_workload2_full_size_sampled_outputs():
         for job in {jobs[0], jobs[-1], *rng.choice(jobs, 2)}:
             q = dp.pool.job_query(job)
             blob = dp.read(q.persist_off, P)
-            W = [blob[o_:o_ + s].view(np.uint16).reshape(k, n)
-                 for o_, s, (k, n) in zip(w_offs, w_sizes, zip(DIMS[:-1], DIMS[1:]))]
+            W = [blob[o_:o_ + s].view(np.uint16) for o_, s in zip(w_offs, w_sizes)]
+            W = [np.ascontiguousarray(w.reshape(n // 128, k, 128).transpose(1, 0, 2)).reshape(k, n) if strip
+                 else w.reshape(k, n) for w, (k, n) in zip(W, zip(DIMS[:-1], DIMS[1:]))]
             ref = dense.mlp_forward_bf16(X[job], W, acts)[-1]
             b = X[job].shape[0]
             Y = dp.read(q.lane_off + y_off, b * DIMS[-1] * 4, np.float32).reshape(b, DIMS[-1])

@@ -103,12 +103,15 @@ def run_jobs(jobs, dtype):
         if dtype == salus.BF16:
             Ws = [synth.f32_to_bf16_bits(w) for w in Ws]
             X = synth.f32_to_bf16_bits(X)
-        for w, off in zip(Ws, w_offs):
-            dp.write(q.persist_off + off, w)
+        # "strip": layers whose width allows it are stored in 128-column strips
+        lay = [salus.LAYOUT_STRIP128 if j.get("strip") and dtype == salus.BF16 and w.shape[1] % 128 == 0
+               else salus.LAYOUT_ROWMAJOR for w in Ws]
+        for w, off, l in zip(Ws, w_offs, lay):
+            dp.write(q.persist_off + off, salus.pack_strip128(w) if l else w)
         dp.write(q.lane_off + x_off, X)
         items.append(dict(job=jid, M=M, dtype=dtype, x_off=x_off, y_off=y_off, h_off=h_off,
-                          layers=[(K, N, off, a) for K, N, off, a in
-                                  zip(dims[:-1], dims[1:], w_offs, j["acts"])]))
+                          layers=[(K, N, off, a, l) for K, N, off, a, l in
+                                  zip(dims[:-1], dims[1:], w_offs, j["acts"], lay)]))
         fwd = dense.mlp_forward_bf16 if dtype == salus.BF16 else dense.mlp_forward_f32
         refs.append(fwd(X, Ws, j["acts"])[-1])
     # poison the outputs so that an unwritten element shows
@@ -191,6 +194,32 @@ def test_bf16_mid_sized_batches_go_tiled_when_the_round_fills_the_chip():
     assert launches == 1
     for o, r, j in zip(outs, refs, jobs):
         assert norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
+
+
+@pytest.mark.parametrize("M", [1, 9, 32, 70, 128, 300])
+def test_bf16_strip_layout_gives_the_same_bits_as_row_major(M):
+    """Weights stored in 128-column strips: same arithmetic in the same order, so
+    the outputs equal the row-major ones bit for bit (and the oracle within tolerance)."""
+    shapes = [(64, 128, NONE), (192, 384, RELU), (1024, 256, GELU), (40, 128, NONE), (264, 1024, GELU)]
+    jobs = [dict(M=M, dims=(K, N), acts=[act]) for K, N, act in shapes]
+    jobs.append(dict(M=M, dims=(256, 512, 384, 136), acts=[GELU, RELU, NONE]))     # last layer stays row-major
+    plain, refs, _ = run_jobs(jobs, salus.BF16)
+    strip, refs2, _ = run_jobs([dict(j, strip=True) for j in jobs], salus.BF16)
+    for a, b, r, j in zip(plain, strip, refs, jobs):
+        assert np.array_equal(a, b), j
+        assert norm_rel_err(b, r) < TOL_BF16_TIGHT, j
+
+
+def test_strip_layout_is_validated():
+    dp = DevicePool(1 << 20, policy=salus.POLICY_PACK)
+    a = dp.pool.lane_alloc(65536, 65536, 0, 1)[1]
+    mk = lambda dtype, layers: salus.Pool.make_descs([dict(job=a, M=4, dtype=dtype, x_off=0, y_off=4096,
+                                                           h_off=8192, layers=layers)])[0]
+    assert dp.pool.grouped_forward(mk(salus.BF16, [(64, 128, 0, 0, salus.LAYOUT_STRIP128)])) == salus.OK
+    assert dp.pool.grouped_forward(mk(salus.BF16, [(64, 64, 0, 0, salus.LAYOUT_STRIP128)])) == salus.EINVAL
+    assert dp.pool.grouped_forward(mk(salus.F32, [(64, 128, 0, 0, salus.LAYOUT_STRIP128)])) == salus.EINVAL
+    assert dp.pool.grouped_forward(mk(salus.BF16, [(64, 128, 0, 0, 7)])) == salus.EINVAL
+    dp.close()
 
 
 def test_more_jobs_than_one_launch_holds():

@@ -267,3 +267,18 @@ def test_workload4_schedule_matches_oracle_over_500_rounds():
     assert st["bytes_d2h"] == st["bytes_h2d"] == 9 * (20 * GB // 256 * 256)
     assert [tuple(e) for e in o.events] == g.poll_events()
     g.close()
+
+
+def test_pack_strip128_is_the_documented_permutation():
+    import numpy as np
+    rng = np.random.default_rng(0)
+    for K, N in [(8, 128), (40, 384), (1024, 1024)]:
+        w = rng.integers(0, 1 << 16, (K, N), dtype=np.uint16)
+        got = salus.pack_strip128(w)
+        # element (k, n) sits at (n // 128 * K + k) * 128 + n % 128
+        k, n = np.meshgrid(np.arange(K), np.arange(N), indexing="ij")
+        want = np.empty(K * N, np.uint16)
+        want[(n // 128 * K + k) * 128 + n % 128] = w
+        assert np.array_equal(got, want)
+    with pytest.raises(salus.SalusError):
+        salus.pack_strip128(np.zeros((8, 64), np.uint16))          # N must be a multiple of 128
