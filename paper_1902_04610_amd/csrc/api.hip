@@ -254,6 +254,11 @@ static void forward_scratch(uint32_t M, const salus_layer *layers, uint32_t n_la
     uint32_t max_n = 0;
     for (uint32_t l = 0; l + 1 < n_layers; ++l) max_n = std::max(max_n, layers[l].N);
     *xp_bytes = 0;
+    if (dtype == SALUS_BF16 && M <= kBlockedMaxM) {
+        // blocked order: whole 16-row tiles and whole 32-column k-steps
+        *h_stride = up256((uint64_t)((M + 15) / 16 * 16) * ((max_n + 31) / 32 * 32) * 2);
+        return;
+    }
     *h_stride = up256((uint64_t)M * max_n * (dtype == SALUS_BF16 ? 2 : 4));
 }
 
@@ -346,6 +351,10 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
                 pr.flags = (uint32_t)L.act;
                 if (bf && !last) pr.flags |= kOutBf16;
                 if (L.layout == SALUS_LAYOUT_STRIP128) pr.flags |= kStripW;
+                if (bf && d.M <= kBlockedMaxM) {      // hidden activations in MFMA operand order
+                    if (l > 0) pr.flags |= kInBlocked;
+                    if (!last) pr.flags |= kOutBlocked;
+                }
                 probs.push_back(pr);
             }
             if (probs.empty()) continue;

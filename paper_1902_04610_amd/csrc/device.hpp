@@ -42,6 +42,13 @@ struct Problem {
 constexpr uint32_t kMaxProblems = 64;       // problems per launch (one per wavefront lane)
 constexpr uint32_t kOutBf16 = 1u << 8;      // store Y as bf16 (round to nearest even)
 constexpr uint32_t kMaskPositive = 1u << 9; // multiply Y by [aux > 0] (ReLU derivative)
+// Hidden activations of jobs with at most 32 rows are kept in the order the MFMA
+// A operand wants them, so that a wavefront's activation load is one contiguous
+// kilobyte: 16-byte unit (k-step s, row tile t, k-group g, row c) at index
+// ((s * T + t) * 4 + g) * 16 + c, T = ceil(M / 16), holds H[16 t + c][32 s + 8 g .. + 8].
+constexpr uint32_t kInBlocked = 1u << 11;   // X is in that order
+constexpr uint32_t kOutBlocked = 1u << 12;  // Y (bf16) is written in that order
+constexpr uint32_t kBlockedMaxM = 32;
 constexpr uint32_t kStripW = 1u << 10;      // W is stored in strips of 128 columns: (k, n) at (n/128 * K + k) * 128 + n % 128
 
 // One launch (or several when n > kMaxProblems): Y_g = act(X_g . W_g) for all g.

@@ -100,6 +100,8 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
     const uint32_t ncol_c = col_ok ? ncol : 0u;
     // Row-major W: row pitch N.  Strip layout: the 128 columns of this tile are one
     // contiguous K x 128 block (pitch 128), so a wavefront's k-step is 8 KB in one piece.
+    const bool blocked_in = !TW && (p.flags & kInBlocked);     // implies M <= 32, so tile.m0 == 0
+    const uint32_t xtiles = (M + 15) / 16;
     const bool strip = !TW && (p.flags & kStripW);
     const uint32_t wpitch = strip ? 128u : N;
     const uint16_t *Wc = strip ? W + (size_t)tile.n0 * K + 8 * c : W + ncol_c;
@@ -114,8 +116,15 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
         }
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
-            const uint32_t row = tile.m0 + 16 * t + c;
-            x[t] = *(const u32x4 *)(X + (size_t)(row < M ? row : M - 1) * K + kc);
+            if (blocked_in) {
+                // one contiguous kilobyte per wavefront; a row tile the job does not
+                // have (its rows are never stored) reads the job's last one instead
+                const uint32_t tt = (uint32_t)t < xtiles ? (uint32_t)t : xtiles - 1;
+                x[t] = *(const u32x4 *)(X + (((size_t)(kc >> 5) * xtiles + tt) * 64 + lane) * 8);
+            } else {
+                const uint32_t row = tile.m0 + 16 * t + c;
+                x[t] = *(const u32x4 *)(X + (size_t)(row < M ? row : M - 1) * K + kc);
+            }
         }
     };
     auto compute = [&](const u32x4 (&w)[8], const u32x4 (&xr)[MT], bool k_ok) {
@@ -194,7 +203,14 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
             u32x4 o;
 #pragma unroll
             for (int j = 0; j < 4; ++j) o[j] = bf16_bits(v[2 * j]) | (bf16_bits(v[2 * j + 1]) << 16);
-            *(u32x4 *)((uint16_t *)p.Y + (size_t)row * N + ncol) = o;
+            if (p.flags & kOutBlocked) {
+                // these 8 columns are k-group (ncol / 8) % 4 of k-step ncol / 32 of the next layer
+                const size_t unit = (((size_t)(ncol >> 5) * xtiles + (row >> 4)) * 4 + ((ncol >> 3) & 3)) * 16 +
+                                    (row & 15);
+                *(u32x4 *)((uint16_t *)p.Y + unit * 8) = o;
+            } else {
+                *(u32x4 *)((uint16_t *)p.Y + (size_t)row * N + ncol) = o;
+            }
         } else {
             float *y = (float *)p.Y + (size_t)row * N + ncol;
             *(f32x4 *)y = f32x4{v[0], v[1], v[2], v[3]};
