@@ -9,10 +9,17 @@ One step = one scheduling round: pending flags -> salus_schedule_iteration ->
 salus_grouped_forward (one grouped launch per layer depth).  All inputs are in
 HBM before the timed region.
 
+The weights are stored in the library's 128-column strips (--row-major for the
+plain layout); values and results are the same either way.
+
 Prints ONE JSON line; `value` is TFLOP/s with flops = 2*M*K*N of the true batch
-sizes.  Extra objects: roofline (HBM-bound weight streaming), saturated (all
-64 models at batch 32), switch (evict / restore / compaction bandwidth) and
-cpu_baseline (the CPU oracle on a bounded sample of the same rounds).
+sizes.  Extra objects: roofline (HBM-bound weight streaming; traffic = profiler
+byte counters from the committed summary of this command), saturated (all 64
+models at batch 32), cpu_baseline (the CPU oracle on a bounded sample of the same
+rounds), switch (evict / restore / compaction bandwidth, and the same switch
+overlapped with running lanes), training (packed training step of 8 jobs),
+small_case_latency (the 4-job correctness configuration, per round) and
+batch_sweep (supplemental: the same 64 models at 32 .. 4096 rows each).
 """
 import argparse
 import ctypes
