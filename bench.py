@@ -27,6 +27,7 @@ import json
 import os
 import sys
 import time
+import types
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
@@ -44,53 +45,11 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-switch", action="store_true", help="skip the evict/restore/compaction figures")
-    ap.add_argument("--no-training", action="store_true", help="skip the packed training-step figures")
-    ap.add_argument("--hot-only", action="store_true", help="only the timed packed-iteration loop (for profiling)")
-    ap.add_argument("--poisson-only", action="store_true",
-                    help="with --hot-only: leave out the saturated rounds (for the traffic counters)")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the supplemental batch-size sweep")
-    ap.add_argument("--sweep-only", action="store_true", help="only the supplemental batch-size sweep")
-    ap.add_argument("--overlap-only", action="store_true", help="only the overlapped-switching figures")
-    ap.add_argument("--row-major", action="store_true",
-                    help="store the weights row-major instead of in 128-column strips")
-    ap.add_argument("--train-only", action="store_true", help="only the packed training step (for profiling)")
-    args = ap.parse_args()
-    global STRIP
-    STRIP = not args.row_major
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on exactly one GPU (jobs are packed inside one device); "
-                 "--gpus must be 1")
-
-    import numpy as np
-    import torch
-    from paper_1902_04610_amd import salus, synth
-
-    if not torch.cuda.is_available():
-        sys.exit("bench.py needs a GPU")
-    if args.train_only:
-        torch.cuda.set_device(0)
-        print(json.dumps(training_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
-        return
-    if args.overlap_only:
-        torch.cuda.set_device(0)
-        print(json.dumps(overlap_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
-        return
-    if args.sweep_only:
-        torch.cuda.set_device(0)
-        print(json.dumps(sweep_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
-        return
+def packing(torch, np, salus, synth, stream, K_steps, W_steps, fused):
+    """Workload 2 resident in a pool of its own: returns the handles and a
+    `run(plans, batches, label)` that times K_steps rounds after W_steps."""
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    K_steps, W_steps = args.steps, args.warmup
     rounds = W_steps + K_steps
-
     # ---------------------------------------------------------------- set-up (untimed)
     up = lambda v: (v + 255) // 256 * 256
     w_sizes = [k * n * 2 for k, n in zip(DIMS[:-1], DIMS[1:])]
@@ -103,7 +62,7 @@ def main():
     cap = MODELS * (P + E)
     buf = torch.empty(cap, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
-    pool = salus.Pool(buf.data_ptr(), cap, policy=salus.POLICY_PACK, stream=stream)
+    pool = salus.Pool(buf.data_ptr(), cap, policy=salus.POLICY_PACK, stream=stream, fuse_depths=fused)
     gen = torch.Generator(device=dev)
     gen.manual_seed(1)
     lane_off = []
@@ -177,7 +136,8 @@ def main():
         active = sum(int((b > 0).sum()) for b in batches_per_round[W_steps:])
         flops = 2.0 * mac_per_row * rows
         alg_bytes = active * P + rows * act_bytes_per_row
-        launches = 3 * K_steps
+        assert pool.fused_check() == salus.OK, pool.last_error()
+        launches = (1 if fused else 3) * K_steps
         res = dict(tflops=flops / wall / 1e12, ms_per_step=wall / K_steps * 1e3,
                    kernel_ms_per_launch=kernel_ms / launches,
                    gbs=alg_bytes / (kernel_ms * 1e-3) / 1e9,
@@ -186,6 +146,71 @@ def main():
         log(f"[{label}] {res}")
         return res
 
+
+    return types.SimpleNamespace(pool=pool, buf=buf, cap=cap, P=P, w_offs=w_offs, w_sizes=w_sizes, batches=batches,
+                                 poisson=poisson, saturated=saturated, run=run, mac_per_row=mac_per_row)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-switch", action="store_true", help="skip the evict/restore/compaction figures")
+    ap.add_argument("--no-training", action="store_true", help="skip the packed training-step figures")
+    ap.add_argument("--hot-only", action="store_true", help="only the timed packed-iteration loop (for profiling)")
+    ap.add_argument("--poisson-only", action="store_true",
+                    help="with --hot-only: leave out the saturated rounds (for the traffic counters)")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the supplemental batch-size sweep")
+    ap.add_argument("--sweep-only", action="store_true", help="only the supplemental batch-size sweep")
+    ap.add_argument("--overlap-only", action="store_true", help="only the overlapped-switching figures")
+    ap.add_argument("--row-major", action="store_true",
+                    help="store the weights row-major instead of in 128-column strips")
+    ap.add_argument("--fused", action="store_true",
+                    help="time the depth-fused forward (one launch per round) as the main path, for profiling")
+    ap.add_argument("--latency-only", action="store_true", help="only the small-case latency, both launch modes")
+    ap.add_argument("--train-only", action="store_true", help="only the packed training step (for profiling)")
+    args = ap.parse_args()
+    global STRIP
+    STRIP = not args.row_major
+    fused = args.fused
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (jobs are packed inside one device); "
+                 "--gpus must be 1")
+
+    import numpy as np
+    import torch
+    from paper_1902_04610_amd import salus, synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    if args.train_only:
+        torch.cuda.set_device(0)
+        print(json.dumps(training_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
+        return
+    if args.latency_only:
+        torch.cuda.set_device(0)
+        st = torch.cuda.current_stream().cuda_stream
+        print(json.dumps([latency_figures(torch, salus, synth, st, fused=f) for f in (False, True)]))
+        return
+    if args.overlap_only:
+        torch.cuda.set_device(0)
+        print(json.dumps(overlap_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
+        return
+    if args.sweep_only:
+        torch.cuda.set_device(0)
+        print(json.dumps(sweep_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
+        return
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K_steps, W_steps = args.steps, args.warmup
+    rounds = W_steps + K_steps
+
+    S = packing(torch, np, salus, synth, torch.cuda.current_stream().cuda_stream, K_steps, W_steps, fused)
+    pool, buf, cap, P, w_offs, w_sizes, batches = S.pool, S.buf, S.cap, S.P, S.w_offs, S.w_sizes, S.batches
+    poisson, saturated, run, mac_per_row = S.poisson, S.saturated, S.run, S.mac_per_row
+    stream = torch.cuda.current_stream().cuda_stream
     log(f"pool {cap / 1e9:.2f} GB, {MODELS} models resident, {rounds} rounds planned")
     main_res = run(poisson, batches, "poisson")
     if args.hot_only:
@@ -216,7 +241,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(main_res["gbs"], 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(main_res["gbs"] / HBM_PEAK_GBS, 4),
                      "traffic": profiled_traffic(K_steps, W_steps),
-                     "kernel": "grouped_dense_bf16",
+                     "kernel": "chained_dense" if fused else "grouped_dense_bf16",
                      "avg_launch_ms": round(main_res["kernel_ms_per_launch"], 5),
                      "algorithmic_bytes_per_launch": int(main_res["bytes_per_launch"])},
     }
@@ -280,6 +305,18 @@ def main():
         out["small_case_latency"] = latency_figures(torch, salus, synth, stream)
     if not args.no_sweep and not args.hot_only:
         out["batch_sweep"] = sweep_figures(torch, salus, stream)
+    if not args.hot_only and not fused:
+        # the same rounds as one depth-fused launch each (SALUS_FLAG_FUSE_DEPTHS), for comparison
+        F = packing(torch, np, salus, synth, stream, K_steps, W_steps, True)
+        fp = F.run(F.poisson, F.batches, "fused poisson")
+        fs = F.run(F.saturated, [np.full(MODELS, MAX_BATCH)] * len(F.batches), "fused saturated")
+        out["fused_depths"] = {"what": "the same workload with one launch per round: tiles of layer l+1 wait on "
+                                       "device counters for their job's layer l (bit-identical outputs)",
+                               "ms_per_step": round(fp["ms_per_step"], 4), "hbm_gbs": round(fp["gbs"], 1),
+                               "saturated_ms_per_step": round(fs["ms_per_step"], 4),
+                               "saturated_hbm_gbs": round(fs["gbs"], 1),
+                               "per_depth_ms_per_step": round(main_res["ms_per_step"], 4)}
+        F.pool.close()
     print(json.dumps(out), flush=True)
 
 
@@ -442,7 +479,7 @@ def profiled_traffic(steps, warmup):
     return None
 
 
-def latency_figures(torch, salus, synth, stream, rounds=2000):
+def latency_figures(torch, salus, synth, stream, rounds=2000, fused=False):
     """The small correctness configuration (4 jobs, two 256 x 256 float layers,
     batch 8, two lanes, round-robin): far too small for bandwidth or flops to
     mean anything, so it is reported as latency per scheduling round."""
@@ -450,7 +487,7 @@ def latency_figures(torch, salus, synth, stream, rounds=2000):
     width, batch = w["width"], w["batch"]
     buf = torch.zeros(w["capacity"], dtype=torch.uint8, device="cuda:0")
     pool = salus.Pool(buf.data_ptr(), w["capacity"], granule=w["granule"], policy=salus.POLICY_FAIR,
-                      stream=stream)
+                      stream=stream, fuse_depths=fused)
     wbytes, items = width * width * 4, []
     for j in range(w["jobs"]):
         st, jid = pool.lane_alloc(w["P"], w["E"], 0, 10 ** 9)
@@ -495,7 +532,8 @@ def latency_figures(torch, salus, synth, stream, rounds=2000):
     lat.sort()
     res = {"workload": "4 jobs, two 256 x 256 float layers, batch 8, two lanes, round-robin (2 jobs per round)",
            "us_per_round_back_to_back": round(wall * 1e6, 2),
-           "us_per_round_gpu_median": round(lat[len(lat) // 2] * 1e3, 2), "launches_per_round": 2}
+           "us_per_round_gpu_median": round(lat[len(lat) // 2] * 1e3, 2), "launches_per_round": 1 if fused else 2}
+    assert pool.fused_check() == salus.OK
     log(f"[latency] {res}")
     pool.close()
     return res

@@ -16,8 +16,10 @@
  *  - "device pointer" = address valid on the GPU; "host pointer" = ordinary
  *    process memory.  All sizes and offsets are bytes (uint64_t); offsets are
  *    relative to the pool base.
- *  - The library never allocates device memory.  It owns its metadata and the
- *    pinned host buffers that hold evicted state (unless the caller passes one).
+ *  - The library places nothing in device memory of its own, with one exception:
+ *    a pool created with SALUS_FLAG_FUSE_DEPTHS holds about 20 KB for descriptors
+ *    and completion counters.  It owns its metadata and the pinned host buffers
+ *    that hold evicted state (unless the caller passes one).
  *  - Not thread safe: one scheduler thread drives a pool (the paper's execution
  *    service is a singleton, Section 3.1).
  *  - Calls that change the layout (lane_alloc, lane_free, switch_out, switch_in,
@@ -46,7 +48,8 @@ enum {
     SALUS_ENOTRESIDENT = -3,   /* job's persistent state is not on the device */
     SALUS_EBUSY = -4,          /* two jobs of one lane in the same launch; job or transfer in transit */
     SALUS_ENEVER = -5,         /* P + E > C: the job could not run even alone (Section 4.2) */
-    SALUS_EHIP = -6            /* the HIP runtime reported an error */
+    SALUS_EHIP = -6,           /* the HIP runtime reported an error */
+    SALUS_ETIMEOUT = -7        /* a depth-fused forward gave up waiting (salus_fused_check) */
 };
 
 /* Scheduling policies of Section 4. */
@@ -66,8 +69,11 @@ enum { SALUS_F32 = 0, SALUS_BF16 = 1 };
 /* Pool options.  SHRINK_LANES: when the job with the largest ephemeral peak leaves
  * a lane that other jobs still use, the lane shrinks to the largest remaining
  * peak, so that L_j = max E_i holds as an equality (Section 3.3.2); younger
- * lanes slide up without any copy.  Off by default: Algorithm 1 never shrinks. */
-enum { SALUS_FLAG_SHRINK_LANES = 1 };
+ * lanes slide up without any copy.  Off by default: Algorithm 1 never shrinks.
+ * FUSE_DEPTHS: salus_grouped_forward runs all layer depths of a round in one
+ * launch whose workgroups wait for their job's previous layer on the device,
+ * instead of one launch per depth (see salus_grouped_forward). */
+enum { SALUS_FLAG_SHRINK_LANES = 1, SALUS_FLAG_FUSE_DEPTHS = 2 };
 
 /* How switch_out / switch_in cross the host link. */
 enum { SALUS_COPY_KERNEL = 0,  /* the library's own copy kernel on mapped pinned memory */
@@ -148,6 +154,7 @@ typedef struct {
     uint64_t lanes_opened, lanes_deleted, lanes_moved;
     uint64_t evictions, restores, admitted, queued;
     uint64_t gemm_launches;
+    uint64_t fused_timeouts;   /* salus_fused_check calls that found a wait given up */
 } salus_stats;
 
 enum { SALUS_EV_ADMIT = 0, SALUS_EV_EVICT = 1, SALUS_EV_RESTORE = 2, SALUS_EV_LANE_NEW = 3,
@@ -221,9 +228,29 @@ int32_t salus_schedule_iteration(salus_pool_t *pool, salus_slot *out, uint32_t c
  * (hipStream_t, NULL = default), asynchronously.  Jobs must be resident and
  * belong to pairwise different lanes (SALUS_EBUSY otherwise); every buffer
  * must lie inside the job's lane / persistent block (SALUS_EINVAL).  K and N
- * of every layer must be multiples of 8 (bf16) or 4 (f32). */
+ * of every layer must be multiples of 8 (bf16) or 4 (f32).
+ *
+ * In a pool with SALUS_FLAG_FUSE_DEPTHS the jobs of one dtype run as ONE launch
+ * over all their layers when each has at most 6 layers and, for bf16, at most
+ * 32 rows (otherwise that dtype takes the per-depth launches): the workgroups
+ * of layer l+1 wait on a device counter for the job's layer l, so a job's next
+ * layer starts as soon as its own input is complete and no launch boundary
+ * drains the GPU.  Outputs are bit-identical to the per-depth launches.  The
+ * job's persistent state and iteration boundary are untouched: this is batching
+ * inside one iteration (Section 3.2.2 rules out scheduling below it, not
+ * this).  Fused calls of one pool must be ordered on the device (use one
+ * stream).  The device-side wait is bounded; see salus_fused_check. */
 int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
                               void *stream);
+
+/* After the caller has synchronized the stream: SALUS_OK if every device-side
+ * wait of the fused launches completed since the last check ended normally,
+ * SALUS_ETIMEOUT if one gave up (the outputs of those launches are invalid; the
+ * pool stays usable).  A wait gives up after `polls` polls of about a
+ * microsecond (default 2^21); it cannot happen while workgroups are dispatched
+ * in index order, the bound exists so that no launch can hang. */
+int32_t salus_fused_check(salus_pool_t *pool);
+int32_t salus_fused_spin_limit(salus_pool_t *pool, uint32_t polls);
 
 /* One layer of a training job: bf16 working weights and float master weights,
  * both K x N row-major inside the job's persistent block. */

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsalus.so")
-SOURCES = ["api.hip", "kernels_copy.hip", "kernels_gemm.hip", "kernels_gemm_tiled.hip", "kernels_train.hip", "pool_core.cpp"]
+SOURCES = ["api.hip", "kernels_copy.hip", "kernels_gemm.hip", "kernels_chain.hip", "kernels_gemm_tiled.hip", "kernels_train.hip", "pool_core.cpp"]
 
 
 def build(verbose=False, extra_flags=(), out=LIB):

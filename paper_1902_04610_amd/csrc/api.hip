@@ -103,6 +103,9 @@ struct salus_pool {
     std::string error;
     uint64_t granule = 256;
     uint64_t gemm_launches = 0;
+    Chain *chain = nullptr;                 // SALUS_FLAG_FUSE_DEPTHS: the depth-fused forward's device state
+    uint32_t spin_limit = kChainSpinLimit;
+    uint64_t fused_timeouts = 0;
 };
 
 #define CHECK_POOL(p) \
@@ -144,6 +147,12 @@ int32_t salus_pool_create(void *base, uint64_t capacity, const salus_config *cfg
     p->granule = c.granule;
     p->core.reset(new PoolCore(capacity, c.granule, c.max_lanes, c.policy,
                                (c.flags & SALUS_FLAG_SHRINK_LANES) != 0, &p->ops));
+    if ((c.flags & SALUS_FLAG_FUSE_DEPTHS) && base) {
+        if (chain_create(&p->chain) != hipSuccess) {
+            delete p;
+            return SALUS_EHIP;
+        }
+    }
     *out = p;
     return SALUS_OK;
 }
@@ -157,6 +166,10 @@ int32_t salus_pool_destroy(salus_pool_t *pool)
         (void)hipEventDestroy(kv.second.done);
     }
     pool->ops.inflight.clear();
+    if (pool->chain) {
+        (void)hipDeviceSynchronize();         // no launch may still read the table
+        chain_destroy(pool->chain);
+    }
     delete pool;
     return SALUS_OK;
 }
@@ -330,33 +343,62 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
         depth = std::max(depth, d.n_layers);
     }
     hipStream_t s = (hipStream_t)stream;
-    // one grouped launch per layer depth over all jobs that have that layer
+    auto problem = [&](uint32_t i, uint32_t l) {
+        const salus_gemm_desc &d = descs[i];
+        const salus_layer &L = d.layers[l];
+        const bool last = l + 1 == d.n_layers;
+        const bool bf = d.dtype == SALUS_BF16;
+        Problem pr{};
+        pr.W = res[i].w + L.w_off;
+        pr.X = l == 0 ? res[i].x : res[i].h + ((l - 1) & 1) * res[i].hstride;
+        pr.Y = last ? res[i].y : res[i].h + (l & 1) * res[i].hstride;
+        pr.M = d.M;
+        pr.K = L.K;
+        pr.N = L.N;
+        pr.flags = (uint32_t)L.act;
+        if (bf && !last) pr.flags |= kOutBf16;
+        if (L.layout == SALUS_LAYOUT_STRIP128) pr.flags |= kStripW;
+        if (bf && d.M <= kBlockedMaxM) {      // hidden activations in MFMA operand order
+            if (l > 0) pr.flags |= kInBlocked;
+            if (!last) pr.flags |= kOutBlocked;
+        }
+        return pr;
+    };
     std::vector<Problem> probs;
     for (int dt = SALUS_F32; dt <= SALUS_BF16; ++dt) {
+        // Depth-fused: all layers of all jobs of this type in one launch, if every
+        // job is one the weight-streaming kernels take (bf16: at most 32 rows).
+        if (pool->chain) {
+            bool fits = true, any = false;
+            for (uint32_t i = 0; i < n && fits; ++i) {
+                const salus_gemm_desc &d = descs[i];
+                if (d.dtype != dt) continue;
+                any = true;
+                fits = d.n_layers <= kChainMaxLayers && d.M <= (dt == SALUS_BF16 ? kBlockedMaxM : 0xffffu);
+            }
+            if (any && fits) {
+                std::vector<ChainJob> jobs;
+                for (uint32_t i = 0; i < n; ++i) {
+                    const salus_gemm_desc &d = descs[i];
+                    if (d.dtype != dt) continue;
+                    ChainJob cj{};
+                    cj.key = d.job;
+                    cj.M = d.M;
+                    cj.n_layers = d.n_layers;
+                    for (uint32_t l = 0; l < d.n_layers; ++l) cj.layer[l] = problem(i, l);
+                    jobs.push_back(cj);
+                }
+                hipError_t e = launch_chain(pool->chain, jobs.data(), (uint32_t)jobs.size(), dt == SALUS_BF16,
+                                            pool->spin_limit, s, &pool->gemm_launches);
+                if (e != hipSuccess) return set_error(pool, SALUS_EHIP, hipGetErrorString(e));
+                continue;
+            }
+        }
+        // one grouped launch per layer depth over all jobs that have that layer
         for (uint32_t l = 0; l < depth; ++l) {
             probs.clear();
-            for (uint32_t i = 0; i < n; ++i) {
-                const salus_gemm_desc &d = descs[i];
-                if (d.dtype != dt || l >= d.n_layers) continue;
-                const salus_layer &L = d.layers[l];
-                const bool last = l + 1 == d.n_layers;
-                const bool bf = dt == SALUS_BF16;
-                Problem pr{};
-                pr.W = res[i].w + L.w_off;
-                pr.X = l == 0 ? res[i].x : res[i].h + ((l - 1) & 1) * res[i].hstride;
-                pr.Y = last ? res[i].y : res[i].h + (l & 1) * res[i].hstride;
-                pr.M = d.M;
-                pr.K = L.K;
-                pr.N = L.N;
-                pr.flags = (uint32_t)L.act;
-                if (bf && !last) pr.flags |= kOutBf16;
-                if (L.layout == SALUS_LAYOUT_STRIP128) pr.flags |= kStripW;
-                if (bf && d.M <= kBlockedMaxM) {      // hidden activations in MFMA operand order
-                    if (l > 0) pr.flags |= kInBlocked;
-                    if (!last) pr.flags |= kOutBlocked;
-                }
-                probs.push_back(pr);
-            }
+            for (uint32_t i = 0; i < n; ++i)
+                if (descs[i].dtype == dt && l < descs[i].n_layers) probs.push_back(problem(i, l));
             if (probs.empty()) continue;
             hipError_t e = dt == SALUS_BF16
                                ? launch_grouped_bf16(probs.data(), (uint32_t)probs.size(), false, s, &pool->gemm_launches)
@@ -368,6 +410,23 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
 }
 
 
+
+int32_t salus_fused_check(salus_pool_t *pool)
+{
+    CHECK_POOL(pool);
+    if (!pool->chain) return SALUS_OK;
+    if (chain_take_timeouts(pool->chain) == 0) return SALUS_OK;
+    pool->fused_timeouts += 1;
+    return set_error(pool, SALUS_ETIMEOUT, "a depth-fused forward gave up waiting for a layer's input; "
+                                            "the outputs of the launches since the last check are invalid");
+}
+
+int32_t salus_fused_spin_limit(salus_pool_t *pool, uint32_t polls)
+{
+    CHECK_POOL(pool);
+    pool->spin_limit = polls;
+    return SALUS_OK;
+}
 
 // Scratch layout of a training step inside the lane: H_1 .. H_{L-1} (bf16, kept
 // for the backward pass), then two gradient buffers of M x max_l(N_l) bf16.
@@ -644,6 +703,7 @@ int32_t salus_get_stats(salus_pool_t *pool, salus_stats *out)
     if (!out) return SALUS_EINVAL;
     *out = pool->core->stats;
     out->gemm_launches = pool->gemm_launches;
+    out->fused_timeouts = pool->fused_timeouts;
     out->queued = pool->core->queued();
     return SALUS_OK;
 }

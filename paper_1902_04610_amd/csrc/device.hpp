@@ -63,6 +63,30 @@ hipError_t launch_grouped_bf16_tiled(const Problem *p, uint32_t n, hipStream_t s
                                      uint64_t *launches);
 hipError_t launch_grouped_f32(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches);
 
+// ---- depth-fused forward ------------------------------------------------------
+// One launch for all layer depths of a round; a tile of depth l waits on a
+// completion counter until its job's depth l-1 is stored.
+constexpr uint32_t kChainMaxLayers = 6;       // layer depths one fused launch can hold
+constexpr uint32_t kChainMaxProblems = 256;   // (job, layer) pairs of a launch, plus one filler per depth
+constexpr uint32_t kChainJobSlots = 64;       // jobs per launch; their descriptors stay cached on the device
+constexpr uint32_t kChainSpinLimit = 1u << 21;  // polls (about a microsecond each) before a wait gives up
+struct ChainJob {
+    int64_t key;                      // identifies the job across calls (descriptor cache)
+    uint32_t M;                       // rows in this round, 1 .. 65535
+    uint32_t n_layers;                // 1 .. kChainMaxLayers
+    Problem layer[kChainMaxLayers];   // as for the per-depth launch (M is ignored)
+};
+struct Chain;                         // device table, counters, host mirror: one per pool
+hipError_t chain_create(Chain **out);   // allocates about 20 KB of device memory
+void chain_destroy(Chain *c);
+// All launches of one Chain must be ordered on the device (one stream, or events):
+// consecutive launches alternate between two sets of counters.
+hipError_t launch_chain(Chain *c, const ChainJob *jobs, uint32_t n, bool bf16, uint32_t spin_limit,
+                        hipStream_t stream, uint64_t *launches);
+// 1 if a wait gave up in a launch that has completed since the last call (the
+// caller has synchronized); clears the flag.
+uint32_t chain_take_timeouts(Chain *c);
+
 // ---- training step ------------------------------------------------------------
 struct LossProblem {
     const float *logits;     // M x N

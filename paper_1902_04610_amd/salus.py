@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsalus.so")
 
 OK, QUEUED = 0, 1
-EINVAL, ENOMEM, ENOTRESIDENT, EBUSY, ENEVER, EHIP = -1, -2, -3, -4, -5, -6
+EINVAL, ENOMEM, ENOTRESIDENT, EBUSY, ENEVER, EHIP, ETIMEOUT = -1, -2, -3, -4, -5, -6, -7
 POLICY_FIFO, POLICY_FAIR, POLICY_PRIORITY, POLICY_PACK = 0, 1, 2, 3
 JOB_QUEUED, JOB_RESIDENT, JOB_EVICTED, JOB_DONE = 0, 1, 2, 3
 ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
@@ -20,6 +20,7 @@ F32, BF16 = 0, 1
 COPY_KERNEL, COPY_DMA = 0, 1
 LAYOUT_ROWMAJOR, LAYOUT_STRIP128 = 0, 1
 FLAG_SHRINK_LANES = 1
+FLAG_FUSE_DEPTHS = 2
 
 
 class Config(C.Structure):
@@ -71,7 +72,7 @@ class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in (
         "rounds", "iterations", "bytes_d2h", "bytes_h2d", "bytes_d2d", "moves", "compactions",
         "lanes_opened", "lanes_deleted", "lanes_moved", "evictions", "restores", "admitted",
-        "queued", "gemm_launches")]
+        "queued", "gemm_launches", "fused_timeouts")]
 
 
 class Event(C.Structure):
@@ -87,6 +88,8 @@ _PROTOS = {
     "salus_job_query": [C.c_void_p, C.c_int32, C.POINTER(JobInfo)],
     "salus_job_set_pending": [C.c_void_p, C.c_int32, C.c_uint64],
     "salus_job_set_cost": [C.c_void_p, C.c_int32, C.c_uint64],
+    "salus_fused_check": [C.c_void_p],
+    "salus_fused_spin_limit": [C.c_void_p, C.c_uint32],
     "salus_set_pending_many": [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_uint64), C.c_uint32],
     "salus_job_write": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
     "salus_job_read": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
@@ -147,10 +150,10 @@ class Pool:
     one to one and return plain Python values."""
 
     def __init__(self, base_ptr, capacity, granule=256, max_lanes=0, policy=POLICY_FAIR,
-                 stream=None, copy_engine=COPY_KERNEL, shrink_lanes=False):
+                 stream=None, copy_engine=COPY_KERNEL, shrink_lanes=False, fuse_depths=False):
         self._lib = lib()
         cfg = Config(granule, max_lanes, policy, stream, copy_engine,
-                     FLAG_SHRINK_LANES if shrink_lanes else 0)
+                     (FLAG_SHRINK_LANES if shrink_lanes else 0) | (FLAG_FUSE_DEPTHS if fuse_depths else 0))
         h = C.c_void_p()
         rc = self._lib.salus_pool_create(base_ptr, capacity, C.byref(cfg), C.byref(h))
         if rc != OK:
@@ -198,6 +201,12 @@ class Pool:
 
     def job_set_cost(self, job, cost):
         return self._lib.salus_job_set_cost(self._h, job, cost)
+
+    def fused_check(self):
+        return self._lib.salus_fused_check(self._h)
+
+    def fused_spin_limit(self, polls):
+        return self._lib.salus_fused_spin_limit(self._h, polls)
 
     def set_pending_many(self, jobs_arr, n_arr, count):
         """jobs_arr: ctypes int32 array, n_arr: ctypes uint64 array."""

@@ -82,14 +82,15 @@ def test_pattern_fill_and_check():
     assert salus.check_pattern(buf.data_ptr(), n, 100, scratch.data_ptr()) == n // 8
 
 
-def run_jobs(jobs, dtype):
+def run_jobs(jobs, dtype, fuse=False):
     """jobs: list of dict(M, dims, acts).  Builds one pool with a lane per job,
-    runs them as ONE packed iteration and returns (gpu outputs, oracle outputs)."""
+    runs them as ONE packed iteration and returns (gpu outputs, oracle outputs,
+    launches).  fuse: the pool runs all layer depths in one launch."""
     esz = 2 if dtype == salus.BF16 else 4
     layouts = [mlp_layout(j["dims"], esz, j["M"]) for j in jobs]
     cap = sum(l[1] + l[5] for l in layouts) + 4096
     cap = (cap + 255) // 256 * 256
-    dp = DevicePool(cap, policy=salus.POLICY_PACK)
+    dp = DevicePool(cap, policy=salus.POLICY_PACK, fuse_depths=fuse)
     rng = np.random.default_rng(len(jobs) * 100 + jobs[0]["M"])
     items, refs = [], []
     for j, (w_offs, P, x_off, y_off, h_off, E) in zip(jobs, layouts):
@@ -123,6 +124,7 @@ def run_jobs(jobs, dtype):
     descs, keep = salus.Pool.make_descs(items)
     assert dp.pool.grouped_forward(descs, stream=dp.stream) == salus.OK
     dp.sync()
+    assert dp.pool.fused_check() == salus.OK
     outs = []
     for it, j in zip(items, jobs):
         q = dp.pool.job_query(it["job"])
