@@ -36,9 +36,10 @@ def bad_words(dp, off, nbytes, seed, scratch):
 
 
 # --------------------------------------------------------------------------- workload 2
-@pytest.mark.parametrize("strip", [False, True])
-def test_workload2_full_size_sampled_outputs(strip):
-    """strip: the weights are stored in 128-column strips, as the benchmark stores them."""
+@pytest.mark.parametrize("strip,fuse", [(False, False), (True, False), (True, True)])
+def test_workload2_full_size_sampled_outputs(strip, fuse):
+    """strip: the weights are stored in 128-column strips, as the benchmark stores them.
+    fuse: one launch per round over all layer depths instead of one per depth."""
     DIMS, MODELS, ROUNDS = (1024, 4096, 1024, 1024), 64, 6
     layout = salus.LAYOUT_STRIP128 if strip else salus.LAYOUT_ROWMAJOR
     acts = [salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE]
@@ -50,7 +51,7 @@ def test_workload2_full_size_sampled_outputs(strip):
     h_off = y_off + up(32 * DIMS[-1] * 4)
     E = up(h_off + salus.forward_work_bytes(32, [(k, n, 0, 0) for k, n in zip(DIMS[:-1], DIMS[1:])],
                                             salus.BF16))
-    dp = big_pool(MODELS * (P + E), policy=salus.POLICY_PACK)
+    dp = big_pool(MODELS * (P + E), policy=salus.POLICY_PACK, fuse_depths=fuse)
     o = op.Pool(MODELS * (P + E), policy=op.PACK)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(1)
@@ -90,6 +91,7 @@ def test_workload2_full_size_sampled_outputs(strip):
         descs, keep = salus.Pool.make_descs(items)
         assert dp.pool.grouped_forward(descs, stream=dp.stream) == salus.OK
         dp.sync()
+        assert dp.pool.fused_check() == salus.OK
         # every output element was written and is finite
         for it in items:
             q = dp.pool.job_query(it["job"])
@@ -109,7 +111,7 @@ def test_workload2_full_size_sampled_outputs(strip):
             worst = max(worst, norm_rel_err(Y, ref))
             checked += 1
     assert checked >= 3 * ROUNDS and worst < TOL_BF16 and worst < TOL_BF16_TIGHT, worst
-    assert dp.pool.stats()["gemm_launches"] == 3 * ROUNDS
+    assert dp.pool.stats()["gemm_launches"] == (1 if fuse else 3) * ROUNDS
     dp.close()
 
 
