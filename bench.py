@@ -381,7 +381,7 @@ def training_figures(torch, salus, stream, jobs=8, dims=(2048, 2048, 2048, 2048,
     res = {"workload": f"{jobs} training jobs, MLP {'-'.join(map(str, dims))}, batch {M}, bf16 + float master, SGD",
            "ms_per_step": round(wall * 1e3, 4), "tflops": round(flops / wall / 1e12, 2),
            "hbm_gbs": round(alg_bytes / wall / 1e9, 1), "hbm_frac": round(alg_bytes / wall / 1e9 / HBM_PEAK_GBS, 4),
-           "launches_per_step": 12, "loss_job0_after": round(loss, 4)}
+           "launches_per_step": 9, "loss_job0_after": round(loss, 4)}
     log(f"[training] {res}")
     pool.close()
     return res

@@ -429,7 +429,9 @@ int32_t salus_fused_spin_limit(salus_pool_t *pool, uint32_t polls)
 }
 
 // Scratch layout of a training step inside the lane: H_1 .. H_{L-1} (bf16, kept
-// for the backward pass), then two gradient buffers of M x max_l(N_l) bf16.
+// for the backward pass), then one gradient buffer of M x max_l(N_l) bf16 per layer
+// (at least two): every layer's incoming gradient stays until the single launch
+// at the end of the step that updates all layers.
 uint64_t salus_train_work_bytes(uint32_t M, const salus_train_layer *layers, uint32_t n_layers)
 {
     if (!layers || n_layers == 0) return 0;
@@ -438,7 +440,7 @@ uint64_t salus_train_work_bytes(uint32_t M, const salus_train_layer *layers, uin
         if (l + 1 < n_layers) total += up256((uint64_t)M * layers[l].N * 2);
         max_n = std::max<uint64_t>(max_n, layers[l].N);
     }
-    return total + 2 * up256((uint64_t)M * max_n * 2);
+    return total + std::max<uint64_t>(n_layers, 2) * up256((uint64_t)M * max_n * 2);
 }
 
 int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *descs, uint32_t n,
@@ -453,7 +455,7 @@ int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *des
     struct Resolved {
         char *persist, *lane;
         std::vector<uint64_t> h_off;   // lane offset of H_l, l = 0 (= x) .. L-1
-        uint64_t g_off[2];
+        std::vector<uint64_t> g_off;   // gradient buffer of backward step 0 .. L-1 (at least two)
     };
     std::vector<Resolved> res(n);
     std::vector<int32_t> lanes_used;
@@ -511,7 +513,8 @@ int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *des
             }
             max_n = std::max<uint64_t>(max_n, d.layers[l].N);
         }
-        for (int b = 0; b < 2; ++b) R.g_off[b] = at + b * up256((uint64_t)d.M * max_n * 2);
+        for (uint32_t b = 0; b < std::max<uint32_t>(d.n_layers, 2); ++b)
+            R.g_off.push_back(at + b * up256((uint64_t)d.M * max_n * 2));
         depth = std::max(depth, d.n_layers);
     }
     hipError_t e = hipSuccess;
@@ -554,26 +557,28 @@ int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *des
         e = launch_softmax_xent(lp.data(), (uint32_t)lp.size(), stream, count);
     }
     // backward: layer `back` counted from each job's last layer, so that jobs of
-    // different depth still share launches; input gradient first (it reads the
-    // weights the update is about to overwrite).  (Running the updates on a second
-    // stream, overlapped with the next input gradient, was measured slower: the
-    // cross-stream waits cost more than the overlap wins.)
+    // different depth still share launches.  First the chain of input gradients
+    // (step `back` reads gradient buffer `back`, writes `back + 1`), then ONE launch
+    // that updates every layer of every job: the updates overwrite weights the input
+    // gradients read, and one grid of all layers ramps up and drains once instead
+    // of once per layer.  (Measured slower, so not done: the update of a layer on a
+    // second stream, or in the same launch, beside the next input gradient - under
+    // the update's HBM stream the latency-bound input gradient takes 3 - 4 times as
+    // long as alone and the launch waits for it.)
     std::vector<UpdateProblem> ups;
     for (uint32_t back = 0; back < depth && e == hipSuccess; ++back) {
         probs.clear();
-        ups.clear();
         for (uint32_t i = 0; i < n; ++i) {
             const salus_train_desc &d = descs[i];
             if (back >= d.n_layers) continue;
             const uint32_t l = d.n_layers - 1 - back;
             const salus_train_layer &L = d.layers[l];
-            char *g_cur = res[i].lane + res[i].g_off[back & 1];
-            char *g_next = res[i].lane + res[i].g_off[(back + 1) & 1];
+            char *g_cur = res[i].lane + res[i].g_off[back];
             if (l > 0) {
                 Problem pr{};
                 pr.W = res[i].persist + L.wb_off;      // K x N: rows are the output columns of dX
                 pr.X = g_cur;
-                pr.Y = g_next;
+                pr.Y = res[i].lane + res[i].g_off[back + 1];
                 pr.aux = res[i].lane + res[i].h_off[l];
                 pr.M = d.M;
                 pr.K = L.N;
@@ -593,8 +598,8 @@ int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *des
             ups.push_back(up);
         }
         if (!probs.empty()) e = launch_grouped_bf16(probs.data(), (uint32_t)probs.size(), true, stream, count);
-        if (e == hipSuccess) e = launch_grouped_dw_sgd(ups.data(), (uint32_t)ups.size(), stream, count);
     }
+    if (e == hipSuccess) e = launch_grouped_dw_sgd(ups.data(), (uint32_t)ups.size(), stream, count);
     if (e != hipSuccess) return set_error(pool, SALUS_EHIP, hipGetErrorString(e));
     return SALUS_OK;
 }

@@ -56,7 +56,11 @@ constexpr int reduce_lds_floats() { return kWaves * 3 * (NACC < 16 ? NACC : 16) 
 // TW (backward pass, dX = dY . W^T): W is stored N x K, so the eight k-values of
 // output column n0+8c+i are contiguous in row n0+8c+i and are loaded as they are.
 // ---------------------------------------------------------------------------
-template <int MT, bool TW>
+// NT: every weight is read by one workgroup only (each job has a single row tile),
+// so the loads carry the non-temporal hint and do not displace activations in
+// L2.  With several row tiles per column tile the neighbours read the same
+// weights at about the same time and a plain load lets the second one hit in L2.
+template <int MT, bool TW, bool NT>
 __device__ inline void dense_bf16_tile(const Problem &p, const Tile tile, float *lds)
 {
     constexpr int NACC = MT * 8;
@@ -96,7 +100,7 @@ __device__ inline void dense_bf16_tile(const Problem &p, const Tile tile, float 
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const uint16_t *at = TW ? W + (size_t)(ncol_c + r) * K + kc : Wc + (size_t)(kc + r) * wpitch;
-            w[r] = __builtin_nontemporal_load((const u32x4 *)at);
+            w[r] = NT ? __builtin_nontemporal_load((const u32x4 *)at) : *(const u32x4 *)at;
         }
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
@@ -186,7 +190,7 @@ __device__ inline void dense_bf16_tile(const Problem &p, const Tile tile, float 
         if (p.flags & kOutBf16) {
             u32x4 o;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) o[j] = bf16_bits(v[2 * j]) | (bf16_bits(v[2 * j + 1]) << 16);
+            for (int j = 0; j < 4; ++j) o[j] = bf16_pack(v[2 * j], v[2 * j + 1]);
             if (p.flags & kOutBlocked) {
                 // these 8 columns are k-group (ncol / 8) % 4 of k-step ncol / 32 of the next layer
                 const size_t unit = (((size_t)(ncol >> 5) * xtiles + (row >> 4)) * 4 + ((ncol >> 3) & 3)) * 16 +

@@ -24,12 +24,18 @@ __device__ inline float activate(float z, uint32_t act)
     return z;
 }
 
-// float -> bf16 bits, round to nearest, ties to even.
+// float -> bf16 bits, round to nearest, ties to even (v_cvt_pk_bf16_f32).
 __device__ inline uint32_t bf16_bits(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
+}
+
+// two floats -> two bf16 in one dword (a in the low half), one instruction
+__device__ inline uint32_t bf16_pack(float a, float b)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
 }
 
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); map

@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kGemmThreads) void chained_dense(ChainArgs a)
     ChainWork w;
     if (!chain_find<16 * MT, BF16 ? 128 : 64>(a, w)) return;
     chain_wait(a, w.pair);
-    if (BF16) dense_bf16_tile<MT, false>(w.p, w.tile, lds);
+    if (BF16) dense_bf16_tile<MT, false, true>(w.p, w.tile, lds);   // at most 32 rows: one row tile
     else dense_f32_tile<MT>(w.p, w.tile, lds);
     if (w.layer + 1 < a.n_layers) chain_signal(a, w.pair);
 }

@@ -18,12 +18,12 @@
 
 namespace salus {
 
-template <int MT, bool TW>
+template <int MT, bool TW, bool NT>
 __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
 {
     __shared__ float lds[reduce_lds_floats<MT * 8>()];
     const Tile tile = find_tile<16 * MT, 128>(a);
-    dense_bf16_tile<MT, TW>(a.p[tile.problem], tile, lds);
+    dense_bf16_tile<MT, TW, NT>(a.p[tile.problem], tile, lds);
 }
 
 template <int MT>
@@ -89,12 +89,18 @@ hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipSt
     }
     auto launch = [&](int mt, const GroupArgs &a, uint32_t tiles) {
         const dim3 grid(tiles), block(kGemmThreads);
+        // mt == 1 means no job has more than 16 rows; with mt == 2 a job above 32
+        // rows has several row tiles that read the same weights
+        bool one_row_tile = true;
+        for (uint32_t i = 0; i < a.n; ++i) one_row_tile = one_row_tile && a.p[i].M <= 16u * mt;
         if (trans_w) {
-            if (mt == 1) hipLaunchKernelGGL((grouped_dense_bf16<1, true>), grid, block, 0, stream, a);
-            else hipLaunchKernelGGL((grouped_dense_bf16<2, true>), grid, block, 0, stream, a);
+            if (mt == 1) hipLaunchKernelGGL((grouped_dense_bf16<1, true, true>), grid, block, 0, stream, a);
+            else if (one_row_tile) hipLaunchKernelGGL((grouped_dense_bf16<2, true, true>), grid, block, 0, stream, a);
+            else hipLaunchKernelGGL((grouped_dense_bf16<2, true, false>), grid, block, 0, stream, a);
         } else {
-            if (mt == 1) hipLaunchKernelGGL((grouped_dense_bf16<1, false>), grid, block, 0, stream, a);
-            else hipLaunchKernelGGL((grouped_dense_bf16<2, false>), grid, block, 0, stream, a);
+            if (mt == 1) hipLaunchKernelGGL((grouped_dense_bf16<1, false, true>), grid, block, 0, stream, a);
+            else if (one_row_tile) hipLaunchKernelGGL((grouped_dense_bf16<2, false, true>), grid, block, 0, stream, a);
+            else hipLaunchKernelGGL((grouped_dense_bf16<2, false, false>), grid, block, 0, stream, a);
         }
     };
     // Row tiles of at most 32 rows: a 64-row tile halves the workgroup count and

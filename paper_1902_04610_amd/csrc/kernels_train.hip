@@ -8,20 +8,13 @@
 // every launch here, as in the forward pass.
 #include <algorithm>
 
-#include "device.hpp"
-#include "wave.hpp"
+#include "group.hpp"
 
 namespace salus {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-__device__ inline uint32_t bf16_rne(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
+__device__ inline uint32_t bf16_rne(float f) { return bf16_bits(f); }
 
 __device__ inline float wave_max(float v)
 {
@@ -39,11 +32,14 @@ __device__ inline float wave_sum(float v)
 
 // ---------------------------------------------------------------------------
 // Mean softmax cross-entropy over the M rows of each job and its gradient
-// (softmax - onehot) / M, written as bf16 for the backward products.  One
-// wavefront per row (a workgroup takes four rows of one job; the job is found
-// with the scan + ballot used everywhere else); each row's loss goes to a
-// scratch array and a second, tiny kernel adds the rows of a job in order, so
-// the result does not depend on how the rows were scheduled.
+// (softmax - onehot) / M, written as bf16 for the backward products.  A
+// workgroup of 16 wavefronts takes 64 rows of one job (the job is found with the
+// scan + ballot used everywhere else), one wavefront four rows.  Rows of up to
+// 1024 classes are read once and kept in registers (all four rows' loads are in
+// flight together); wider rows are re-read from memory for each of the three
+// passes.  Row losses are added in row order by one thread, so the result does
+// not depend on how the rows were scheduled: inside the workgroup when it holds
+// the whole job, else by a second, tiny kernel over the scratch array.
 // ---------------------------------------------------------------------------
 struct LossArgs {
     uint32_t n;
@@ -51,40 +47,117 @@ struct LossArgs {
     LossProblem p[kMaxProblems];
 };
 
-__global__ __launch_bounds__(256) void softmax_xent_rows(LossArgs a)
+constexpr int kLossRows = 64, kLossWaves = 16, kLossPerWave = kLossRows / kLossWaves, kLossRegs = 16;
+
+__global__ __launch_bounds__(64 * kLossWaves) void softmax_xent_rows(LossArgs a)
 {
+    __shared__ float row_loss[kLossRows];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool valid = lane < (int)a.n;
-    const uint32_t blocks = valid ? (a.p[lane].M + 3) / 4 : 0;
+    const uint32_t blocks = valid ? (a.p[lane].M + kLossRows - 1) / kLossRows : 0;
     const uint32_t first = wave_excl_scan_u32(blocks, nullptr);
     const int job = __builtin_amdgcn_readfirstlane(wave_find_range(first, blockIdx.x, valid));
     const LossProblem &p = a.p[job];
-    const uint32_t row = (blockIdx.x - __shfl(first, job, 64)) * 4 + wave;
+    const uint32_t row0 = (blockIdx.x - __shfl(first, job, 64)) * kLossRows;
     const uint32_t M = p.M, N = p.N;
-    if (row >= M) return;
     const float inv_m = 1.0f / (float)M;
-    const float *z = p.logits + (size_t)row * N;
-    float zmax = -INFINITY;
-    for (uint32_t n = lane; n < N; n += 64) zmax = fmaxf(zmax, z[n]);
-    zmax = wave_max(zmax);
-    float denom = 0.0f;
-    for (uint32_t n = lane; n < N; n += 64) denom += expf(z[n] - zmax);
-    denom = wave_sum(denom);
-    int label = p.labels[row];
-    label = label < 0 ? 0 : (label >= (int)N ? (int)N - 1 : label);    // never read outside the row
-    if (lane == 0) p.row_loss[row] = -(z[label] - zmax - logf(denom));
-    uint16_t *g = (uint16_t *)p.grad + (size_t)row * N;
-    const float inv_d = 1.0f / denom;
-    for (uint32_t n = lane; n < N; n += 64) {
-        const float prob = expf(z[n] - zmax) * inv_d;
-        g[n] = (uint16_t)bf16_rne((prob - ((int)n == label ? 1.0f : 0.0f)) * inv_m);
+    // register path: lane owns classes 256 i + 4 lane .. + 3 of a row (16-byte loads, 8-byte stores)
+    const bool in_regs = N <= 64u * kLossRegs && N % 4 == 0;
+
+    f32x4 zr[kLossPerWave][kLossRegs / 4];
+    int labels[kLossPerWave];
+#pragma unroll
+    for (int q = 0; q < kLossPerWave; ++q) {
+        const uint32_t row = row0 + wave * kLossPerWave + q;
+        const int l = p.labels[row < M ? row : M - 1];
+        labels[q] = l < 0 ? 0 : (l >= (int)N ? (int)N - 1 : l);          // never read outside the row
+    }
+    if (in_regs) {
+#pragma unroll
+        for (int q = 0; q < kLossPerWave; ++q) {
+            const uint32_t row = row0 + wave * kLossPerWave + q;
+            const float *z = p.logits + (size_t)(row < M ? row : M - 1) * N;
+#pragma unroll
+            for (int i = 0; i < kLossRegs / 4; ++i) {
+                const uint32_t n = 256u * i + 4u * lane;
+                zr[q][i] = *(const f32x4 *)(z + (n < N ? n : N - 4));
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < kLossPerWave; ++q) {
+        const uint32_t row = row0 + wave * kLossPerWave + q;
+        if (row >= M) continue;                              // uniform per wavefront
+        const float *z = p.logits + (size_t)row * N;
+        uint16_t *g = (uint16_t *)p.grad + (size_t)row * N;
+        const int label = labels[q];
+        float zmax = -INFINITY, denom = 0.0f, zlabel = 0.0f;
+        if (in_regs) {
+#pragma unroll
+            for (int i = 0; i < kLossRegs / 4; ++i)
+                if (256u * i + 4u * lane < N)
+                    zmax = fmaxf(fmaxf(zmax, fmaxf(zr[q][i][0], zr[q][i][1])), fmaxf(zr[q][i][2], zr[q][i][3]));
+            zmax = wave_max(zmax);
+            f32x4 e[kLossRegs / 4];
+#pragma unroll
+            for (int i = 0; i < kLossRegs / 4; ++i) {
+                // v_exp_f32: error at the last-bit level, far below the bf16 rounding of the gradient
+#pragma unroll
+                for (int j = 0; j < 4; ++j) e[i][j] = __expf(zr[q][i][j] - zmax);
+                if (256u * i + 4u * lane < N) denom += (e[i][0] + e[i][1]) + (e[i][2] + e[i][3]);
+            }
+            denom = wave_sum(denom);
+            const float inv_d = 1.0f / denom;
+#pragma unroll
+            for (int i = 0; i < kLossRegs / 4; ++i) {
+                const uint32_t n = 256u * i + 4u * lane;
+                if (n >= N) continue;
+                float h[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool hit = (int)(n + j) == label;
+                    if (hit) zlabel = zr[q][i][j];
+                    h[j] = (e[i][j] * inv_d - (hit ? 1.0f : 0.0f)) * inv_m;
+                }
+                *(u32x2 *)(g + n) = u32x2{bf16_pack(h[0], h[1]), bf16_pack(h[2], h[3])};
+            }
+            // the lane that holds the label's class hands its logit to lane 0
+            zlabel = __shfl(zlabel, (label & 255) >> 2, 64);
+        } else {
+            for (uint32_t n = lane; n < N; n += 64) zmax = fmaxf(zmax, z[n]);
+            zmax = wave_max(zmax);
+            for (uint32_t n = lane; n < N; n += 64) denom += expf(z[n] - zmax);
+            denom = wave_sum(denom);
+            const float inv_d = 1.0f / denom;
+            for (uint32_t n = lane; n < N; n += 64) {
+                const float prob = expf(z[n] - zmax) * inv_d;
+                g[n] = (uint16_t)bf16_rne((prob - ((int)n == label ? 1.0f : 0.0f)) * inv_m);
+            }
+        }
+        if (!in_regs) zlabel = z[label];
+        if (lane == 0) {
+            const float loss = -(zlabel - zmax - logf(denom));
+            row_loss[row - row0] = loss;
+            if (M > (uint32_t)kLossRows) p.row_loss[row] = loss;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && M <= (uint32_t)kLossRows) {      // this workgroup holds the whole job
+        float sum = 0.0f;
+#pragma unroll
+        for (uint32_t r = 0; r < (uint32_t)kLossRows; ++r) {
+            const float v = row_loss[r < M ? r : 0];
+            if (r < M) sum += v;
+        }
+        *p.loss = sum / (float)M;
     }
 }
 
+// Jobs of more than 64 rows: add the row losses of each in row order.
 __global__ __launch_bounds__(64) void loss_mean(LossArgs a)
 {
     const LossProblem &p = a.p[blockIdx.x];
-    if (threadIdx.x != 0) return;
+    if (threadIdx.x != 0 || p.M <= (uint32_t)kLossRows) return;
     float sum = 0.0f;
     for (uint32_t r = 0; r < p.M; ++r) sum += p.row_loss[r];
     *p.loss = sum / (float)p.M;
@@ -96,14 +169,16 @@ hipError_t launch_softmax_xent(const LossProblem *p, uint32_t n, hipStream_t str
         LossArgs a{};
         a.n = std::min(kMaxProblems, n - at);
         uint64_t blocks = 0;
+        bool big = false;
         for (uint32_t i = 0; i < a.n; ++i) {
             a.p[i] = p[at + i];
-            blocks += (a.p[i].M + 3) / 4;
+            blocks += (a.p[i].M + kLossRows - 1) / kLossRows;
+            big = big || a.p[i].M > (uint32_t)kLossRows;
         }
         if (blocks == 0) continue;
         if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(softmax_xent_rows, dim3((uint32_t)blocks), dim3(256), 0, stream, a);
-        hipLaunchKernelGGL(loss_mean, dim3(a.n), dim3(64), 0, stream, a);
+        hipLaunchKernelGGL(softmax_xent_rows, dim3((uint32_t)blocks), dim3(64 * kLossWaves), 0, stream, a);
+        if (big) hipLaunchKernelGGL(loss_mean, dim3(a.n), dim3(64), 0, stream, a);
         if (launches) *launches += 1;
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -134,22 +209,28 @@ struct UpdateArgs {
 
 constexpr int kUpdK = 64, kUpdN = 256;      // workgroup tile
 
-__global__ __launch_bounds__(256) void grouped_dw_sgd(UpdateArgs a)
+// Which update problem and tile workgroup `id` owns: lane i holds job i's tile count.
+__device__ inline int find_update(const UpdateProblem *p, uint32_t n, uint32_t id, uint32_t *t, uint32_t *kt)
+{
+    const int lane = threadIdx.x & 63;
+    const bool valid = lane < (int)n;
+    uint32_t k_tiles = 0, count = 0;
+    if (valid) {
+        k_tiles = (p[lane].K + kUpdK - 1) / kUpdK;
+        count = k_tiles * ((p[lane].N + kUpdN - 1) / kUpdN);
+    }
+    const uint32_t first = wave_excl_scan_u32(count, nullptr);
+    const int job = __builtin_amdgcn_readfirstlane(wave_find_range(first, id, valid));
+    *t = id - __shfl(first, job, 64);
+    *kt = __shfl(k_tiles, job, 64);
+    return job;
+}
+
+// Tile t of one job's update (kt = its number of 64-row tiles).
+__device__ inline void dw_sgd_tile(const UpdateProblem &p, uint32_t t, uint32_t kt)
 {
     const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // job lookup: lane i holds job i's tile count
-    const bool valid = lane < (int)a.n;
-    uint32_t k_tiles = 0, count = 0;
-    if (valid) {
-        k_tiles = (a.p[lane].K + kUpdK - 1) / kUpdK;
-        count = k_tiles * ((a.p[lane].N + kUpdN - 1) / kUpdN);
-    }
-    const uint32_t first = wave_excl_scan_u32(count, nullptr);
-    const int job = __builtin_amdgcn_readfirstlane(wave_find_range(first, blockIdx.x, valid));
-    const uint32_t t = blockIdx.x - __shfl(first, job, 64);
-    const uint32_t kt = __shfl(k_tiles, job, 64);
-    const UpdateProblem &p = a.p[job];
     const uint32_t M = p.M, K = p.K, N = p.N;
     const uint32_t k0 = (t % kt) * kUpdK;                  // neighbours share the G columns
     const uint32_t n0 = (t / kt) * kUpdN + 64 * wave;
@@ -214,10 +295,17 @@ __global__ __launch_bounds__(256) void grouped_dw_sgd(UpdateArgs a)
                 w[j] = __fsub_rn(w[j], __fmul_rn(lr, acc[i * 4 + j][r]));
             __builtin_nontemporal_store(w, (f32x4 *)(p.Wm + (size_t)krow * N + ncol));
             u32x2 b;
-            b[0] = bf16_rne(w[0]) | (bf16_rne(w[1]) << 16);
-            b[1] = bf16_rne(w[2]) | (bf16_rne(w[3]) << 16);
+            b[0] = bf16_pack(w[0], w[1]);
+            b[1] = bf16_pack(w[2], w[3]);
             *(u32x2 *)((uint16_t *)p.Wb + (size_t)krow * N + ncol) = b;
         }
+}
+
+__global__ __launch_bounds__(256) void grouped_dw_sgd(UpdateArgs a)
+{
+    uint32_t t, kt;
+    const int job = find_update(a.p, a.n, blockIdx.x, &t, &kt);
+    dw_sgd_tile(a.p[job], t, kt);
 }
 
 hipError_t launch_grouped_dw_sgd(const UpdateProblem *p, uint32_t n, hipStream_t stream,

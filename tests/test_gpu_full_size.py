@@ -255,7 +255,7 @@ def test_workload3_full_size_sampled_job():
     descs, keep = salus.Pool.make_train_descs(j.desc() for j in jobs)
     assert dp.pool.grouped_train_step(descs, stream=dp.stream) == salus.OK
     dp.sync()
-    assert dp.pool.stats()["gemm_launches"] == 4 + 1 + 3 + 4
+    assert dp.pool.stats()["gemm_launches"] == 4 + 1 + 3 + 1      # forward, loss, input gradients, all updates
     for k in (1, 6):
         check_step_stagewise(jobs[k], *batches[k])
     dp.close()

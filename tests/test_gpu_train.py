@@ -47,7 +47,7 @@ class TrainJob:
         self.loss_off = self.logits_off + up(M * dims[-1] * 4)
         self.work_off = self.loss_off + 256
         work = salus.train_work_bytes(M, self.layers)
-        assert work == sum(up(M * n * 2) for n in dims[1:-1]) + 2 * up(M * max(dims[1:]) * 2)
+        assert work == sum(up(M * n * 2) for n in dims[1:-1]) + max(len(dims) - 1, 2) * up(M * max(dims[1:]) * 2)
         self.E = self.work_off + work
         st, self.job = dp.pool.lane_alloc(self.P, self.E, 0, 10 ** 6)
         assert st == salus.OK
@@ -156,7 +156,7 @@ def run(configs, steps, seed):
         specs.append((dims, M, lr, Wm))
         cap += sum(up(K * N * 2) + up(K * N * 4) for K, N in zip(dims[:-1], dims[1:]))
         cap += up(M * dims[0] * 2) + up(M * 4) + up(M * dims[-1] * 4) + 256 + \
-            sum(up(M * n * 2) for n in dims[1:-1]) + 2 * up(M * max(dims[1:]) * 2) + 4096
+            sum(up(M * n * 2) for n in dims[1:-1]) + max(len(dims) - 1, 2) * up(M * max(dims[1:]) * 2) + 4096
     dp = DevicePool(up(cap), policy=salus.POLICY_PACK)
     jobs = [TrainJob(dp, *s) for s in specs]
     descs, keep = salus.Pool.make_train_descs(j.desc() for j in jobs)
@@ -173,8 +173,8 @@ def run(configs, steps, seed):
         assert dp.pool.grouped_train_step(descs, stream=dp.stream) == salus.OK
         dp.sync()
         depth = max(len(j.layers) for j in jobs)
-        # forward + loss + (input gradient, update) per layer, shared by all jobs
-        assert dp.pool.stats()["gemm_launches"] - before == depth + 1 + (depth - 1) + depth
+        # forward + loss + input gradients + ONE update launch for all layers, shared by all jobs
+        assert dp.pool.stats()["gemm_launches"] - before == depth + 1 + (depth - 1) + 1
         for j, (Xb, labels) in zip(jobs, batches):
             check_step(j, Xb, labels, step)
     dp.close()
