@@ -1,4 +1,4 @@
-// Grouped dense layer for jobs that bring many rows (M >= 128, or more than 32
+// Grouped dense layer for jobs that bring many rows (M >= 128, or more than 64
 // when the round holds enough of them to fill the chip with 128-row tiles): the
 // compute-bound counterpart of the weight-streaming kernel.  Same contract (one
 // launch runs one layer of every scheduled job, Salus paper, Section 3.3), but
