@@ -284,8 +284,11 @@ uint64_t salus_train_work_bytes(uint32_t M, const salus_train_layer *layers, uin
  *   loss and dZ_L = (softmax - onehot) / M;
  *   for l = L..1:  G = bf16(dZ_l);  dZ_{l-1} = (G . Wb_l^T) * [H_{l-1} > 0];
  *                  Wm_l <- Wm_l - lr * (H_{l-1}^T . G);  Wb_l <- bf16(Wm_l)
- * with one grouped launch per layer and phase (forward, loss, input gradient,
- * weight update).  ReLU between layers, no biases, plain SGD.  Same residency,
+ * with one grouped launch per layer for the forward pass and for the input
+ * gradients, one for the loss, and one that updates every layer (it runs last:
+ * the updates overwrite weights the input gradients read; every layer's
+ * incoming gradient is kept in the work area until then).  ReLU between
+ * layers, no biases, plain SGD.  Same residency,
  * lane and bounds rules as salus_grouped_forward; K and N multiples of 8. */
 int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *descs, uint32_t n,
                                  void *stream);

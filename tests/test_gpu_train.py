@@ -185,6 +185,14 @@ def test_train_step_ragged_shapes():
          ((128, 128), 1, 0.02)], steps=2, seed=0)
 
 
+def test_train_step_loss_kernel_paths():
+    """More than 64 rows (several workgroups per job, row losses added by the second
+    kernel), more than 1024 classes (rows re-read instead of kept in registers),
+    exactly 1024, and both at once."""
+    run([((72, 40), 70, 0.05), ((64, 1032), 9, 0.05), ((40, 72, 1024), 130, 0.01), ((136, 2056), 66, 0.02),
+         ((64, 8), 64, 0.1)], steps=1, seed=3)
+
+
 def test_train_step_lr_zero_changes_nothing():
     dims, M = (136, 264, 72), 20
     rng = np.random.default_rng(5)
