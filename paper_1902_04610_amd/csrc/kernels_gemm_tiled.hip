@@ -55,21 +55,6 @@ __device__ inline Tile find_tile_banded(const GroupArgs &a)
     return tile;
 }
 
-// erf by the rational approximation 7.1.26 of Abramowitz & Stegun (absolute
-// error below 1.5e-7, far inside half a bf16 step): one reciprocal, one
-// exponential and a degree-5 polynomial, no branches.
-__device__ inline float gelu_fast(float z)
-{
-    const float x = fabsf(z) * 0.70710678118654752440f;
-    const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
-    float q = fmaf(1.061405429f, t, -1.453152027f);
-    q = fmaf(q, t, 1.421413741f);
-    q = fmaf(q, t, -0.284496736f);
-    q = fmaf(q, t, 0.254829592f);
-    const float e = 1.0f - q * t * __expf(-x * x);        // erf(|z| / sqrt 2)
-    return 0.5f * z * (1.0f + copysignf(e, z));
-}
-
 template <int ACT, int FM, int FN>
 __device__ inline void store_tile(const f32x16 (&acc)[FM][FN], const Problem &p, const Tile &tile,
                                   uint32_t wm, uint32_t wn, uint32_t fl, uint32_t fh)
