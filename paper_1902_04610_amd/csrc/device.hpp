@@ -13,7 +13,7 @@ struct CopySeg {
     uint64_t len;        // bytes, multiple of 16; src and dst 16-byte aligned
 };
 constexpr uint32_t kMaxSeg = 64;            // segments per launch (one per wavefront lane)
-constexpr uint32_t kCopyChunk = 16 * 1024;  // bytes one workgroup moves per grid-stride step
+constexpr uint32_t kCopyChunk = 8 * 1024;   // bytes one workgroup moves per grid-stride step
 
 // Copies n mutually independent segments (no destination may overlap another
 // segment's source); more than kMaxSeg segments are split over launches.
