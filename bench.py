@@ -169,6 +169,8 @@ def main():
                     help="store the weights row-major instead of in 128-column strips")
     ap.add_argument("--fused", action="store_true",
                     help="time the depth-fused forward (one launch per round) as the main path, for profiling")
+    ap.add_argument("--switch-only", action="store_true",
+                    help="only evict / restore / compaction (for profiling)")
     ap.add_argument("--latency-only", action="store_true", help="only the small-case latency, both launch modes")
     ap.add_argument("--train-only", action="store_true", help="only the packed training step (for profiling)")
     args = ap.parse_args()
@@ -188,6 +190,10 @@ def main():
     if args.train_only:
         torch.cuda.set_device(0)
         print(json.dumps(training_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
+        return
+    if args.switch_only:
+        torch.cuda.set_device(0)
+        print(json.dumps(switch_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
         return
     if args.latency_only:
         torch.cuda.set_device(0)
