@@ -274,7 +274,8 @@ typedef struct {
 } salus_train_desc;
 
 /* Bytes of lane scratch a training step needs: the hidden activations of every
- * layer (kept for the backward pass) and two gradient buffers. */
+ * layer (kept for the backward pass) and one gradient buffer per layer (at
+ * least two). */
 uint64_t salus_train_work_bytes(uint32_t M, const salus_train_layer *layers, uint32_t n_layers);
 
 /* Packed training iteration (Sections 2.1 and 5.2: forward pass, backward pass
@@ -288,8 +289,8 @@ uint64_t salus_train_work_bytes(uint32_t M, const salus_train_layer *layers, uin
  * gradients, one for the loss, and one that updates every layer (it runs last:
  * the updates overwrite weights the input gradients read; every layer's
  * incoming gradient is kept in the work area until then).  ReLU between
- * layers, no biases, plain SGD.  Same residency,
- * lane and bounds rules as salus_grouped_forward; K and N multiples of 8. */
+ * layers, no biases, plain SGD.  Same residency, lane and bounds rules as
+ * salus_grouped_forward; K and N multiples of 8. */
 int32_t salus_grouped_train_step(salus_pool_t *pool, const salus_train_desc *descs, uint32_t n,
                                  void *stream);
 
