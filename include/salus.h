@@ -239,7 +239,10 @@ int32_t salus_schedule_iteration(salus_pool_t *pool, salus_slot *out, uint32_t c
  * job's persistent state and iteration boundary are untouched: this is batching
  * inside one iteration (Section 3.2.2 rules out scheduling below it, not
  * this).  Fused calls of one pool must be ordered on the device (use one
- * stream).  The device-side wait is bounded; see salus_fused_check. */
+ * stream) and cannot be recorded in a HIP graph (SALUS_EINVAL while the stream
+ * is capturing: consecutive launches alternate between two sets of counters);
+ * the per-depth launches can, they are plain kernel launches with by-value
+ * arguments.  The device-side wait is bounded; see salus_fused_check. */
 int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
                               void *stream);
 

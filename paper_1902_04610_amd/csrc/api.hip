@@ -377,6 +377,11 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
                 fits = d.n_layers <= kChainMaxLayers && d.M <= (dt == SALUS_BF16 ? kBlockedMaxM : 0xffffu);
             }
             if (any && fits) {
+                // its two sets of counters alternate from launch to launch, which a
+                // replayed recording would not do
+                hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+                if (hipStreamIsCapturing(s, &capturing) != hipSuccess || capturing != hipStreamCaptureStatusNone)
+                    return set_error(pool, SALUS_EINVAL, "the depth-fused forward cannot be recorded in a graph");
                 std::vector<ChainJob> jobs;
                 for (uint32_t i = 0; i < n; ++i) {
                     const salus_gemm_desc &d = descs[i];
