@@ -146,7 +146,7 @@ def check_step(job, Xb, labels, step, tol_grad=TOL_GRAD):
     job.Wm, job.Wb = gWm, gWb
 
 
-def run(configs, steps, seed):
+def run(configs, steps, seed, update_launches=1):
     rng = np.random.default_rng(seed)
     cap = 0
     specs = []
@@ -174,7 +174,7 @@ def run(configs, steps, seed):
         dp.sync()
         depth = max(len(j.layers) for j in jobs)
         # forward + loss + input gradients + ONE update launch for all layers, shared by all jobs
-        assert dp.pool.stats()["gemm_launches"] - before == depth + 1 + (depth - 1) + 1
+        assert dp.pool.stats()["gemm_launches"] - before == depth + 1 + (depth - 1) + update_launches
         for j, (Xb, labels) in zip(jobs, batches):
             check_step(j, Xb, labels, step)
     dp.close()
@@ -183,6 +183,11 @@ def run(configs, steps, seed):
 def test_train_step_ragged_shapes():
     run([((72, 136, 264, 40), 13, 0.05), ((264, 72, 8), 64, 0.01), ((40, 520, 136), 33, 0.1),
          ((128, 128), 1, 0.02)], steps=2, seed=0)
+
+
+def test_more_update_problems_than_one_launch_holds():
+    # 24 jobs x 3 layers = 72 (job, layer) updates: two update launches of at most 64
+    run([((40, 72, 48, 16), 1 + k % 9, 0.03) for k in range(24)], steps=1, seed=8, update_launches=2)
 
 
 def test_train_step_loss_kernel_paths():
