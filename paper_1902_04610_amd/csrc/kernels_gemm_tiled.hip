@@ -17,12 +17,14 @@
 // this swizzle each of them spreads every 8 lanes that the LDS serves together
 // over all 8 slots of the 128-byte bank row.
 #include <algorithm>
+#include <vector>
 
 #include "group.hpp"
 
 namespace salus {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBM = 128, kBN = 256, kBK = 64;
 constexpr int kLine = kBK * 2;                 // bytes per LDS line
@@ -246,6 +248,138 @@ __global__ __launch_bounds__(256, 2) void grouped_dense_bf16_tiled(GroupArgs a)
 }
 
 
+// ---------------------------------------------------------------------------
+// The same scheme with a 256 x 256 tile and eight wavefronts (4 x 2, each again
+// 64 x 128), for jobs of at least 192 rows.  Per multiply-add it moves a third
+// less through L2 than the 128 x 256 tile ((256 + 256) / (256 * 256) against
+// (128 + 256) / (128 * 256) operand bytes), which is what bounds the smaller
+// tile: measured, its loads and LDS writes alone take as long as its MFMAs
+// alone.  One workgroup fills a CU's registers, so the overlap of memory and
+// MFMA phases has to come from inside it: LDS holds two slabs (128 KB), the slab
+// after the one being multiplied is written while it is multiplied, the one
+// after that is on its way from memory, and there is one barrier per slab.
+// A thread owns four 16-byte k-chunks of X (rows 64 apart) and a block of 4 k x 8
+// columns of W, which it transposes into eight 8-byte half-chunks.
+// ---------------------------------------------------------------------------
+constexpr int kBM2 = 256, kThreads2 = 512;
+constexpr uint32_t kStageBytes = (kBM2 + kBN) * kLine;      // 64 KB
+
+__global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled256(GroupArgs a)
+{
+    __shared__ __attribute__((aligned(128))) unsigned char smem[2 * kStageBytes];
+    const Tile tile = find_tile_banded<kBM2, kBN>(a);
+    const Problem &p = a.p[tile.problem];
+    const uint32_t M = p.M, K = p.K, N = p.N;
+    const uint32_t t = threadIdx.x, lane = t & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const uint32_t wm = wave >> 1, wn = wave & 1u;
+    const uint16_t *W = (const uint16_t *)p.W;
+    const uint16_t *X = (const uint16_t *)p.X;
+
+    // X: k-chunk ca of rows ra, ra+64, ra+128, ra+192 (lines 64 apart share their swizzle)
+    const uint32_t ca = t & 7u, ra = t >> 3;
+    const uint16_t *xsrc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t row = tile.m0 + ra + 64u * i;
+        xsrc[i] = X + (size_t)(row < M ? row : M - 1) * K + 8u * ca;
+    }
+    const uint32_t xoff = ra * kLine + ((ca ^ swz(ra)) << 4);
+    // W: rows 4*kq .. 4*kq+3 of the slab, columns 8*nb .. 8*nb+7
+    const uint32_t kq = (lane >> 3) + 8u * (wave >> 2), nb = (lane & 7u) + 8u * (wave & 3u);
+    const uint32_t ncol = tile.n0 + 8u * nb, ncol_c = ncol < N ? ncol : 0u;
+    const bool strip = (p.flags & kStripW) != 0;
+    const uint32_t wpitch = strip ? 128u : N;
+    const uint16_t *wsrc = strip ? W + (size_t)(ncol_c & ~127u) * K + (4u * kq) * 128u + (ncol_c & 127u)
+                                 : W + (size_t)(4u * kq) * N + ncol_c;
+    uint32_t woff[8];      // byte offset of this thread's half-chunk in column line 8*nb + i
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t line = 8u * nb + i;
+        woff[i] = (kBM2 + line) * kLine + (((kq >> 1) ^ swz(line)) << 4) + 8u * (kq & 1u);
+    }
+
+    u32x4 xr[4], wr[4];
+    auto load_slab = [&](uint32_t k0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xr[i] = *(const u32x4 *)(xsrc[i] + k0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) wr[r] = *(const u32x4 *)(wsrc + (size_t)(k0 + r) * wpitch);
+    };
+    auto store_slab = [&](uint32_t stage) {
+        unsigned char *base = smem + stage;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *(u32x4 *)(base + xoff + 64 * i * kLine) = xr[i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            u32x2 b;       // column i of the block: dword j = (k 2j, k 2j+1)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                b[j] = __builtin_amdgcn_perm(wr[2 * j + 1][i >> 1], wr[2 * j][i >> 1],
+                                             (i & 1) ? 0x07060302u : 0x05040100u);
+            *(u32x2 *)(base + woff[i]) = b;
+        }
+    };
+
+    const uint32_t fl = lane & 31u, fh = lane >> 5, fs = swz(fl);
+    const uint32_t afrag = (wm * 64u + fl) * kLine;
+    const uint32_t bfrag = (kBM2 + wn * 128u + fl) * kLine;
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const uint32_t slabs = K / kBK;
+    uint32_t cur = 0;
+    load_slab(0);
+    store_slab(0);
+    if (slabs > 1) load_slab(kBK);
+    __syncthreads();
+    for (uint32_t s = 0; s < slabs; ++s) {
+        const unsigned char *base = smem + cur;
+#pragma unroll
+        for (uint32_t ks = 0; ks < 4; ++ks) {
+            const uint32_t off = ((2u * ks + fh) ^ fs) << 4, off_odd = off ^ 64u;
+            bf16x8 av[2], bv[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) av[i] = *(const bf16x8 *)(base + afrag + 32 * i * kLine + (i & 1 ? off_odd : off));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bv[j] = *(const bf16x8 *)(base + bfrag + 32 * j * kLine + (j & 1 ? off_odd : off));
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        if (s + 1 < slabs) {
+            store_slab(cur ^ kStageBytes);       // the other stage: everyone left it at the last barrier
+            if (s + 2 < slabs) load_slab((s + 2) * kBK);
+        }
+        __syncthreads();
+        cur ^= kStageBytes;
+    }
+
+    const uint32_t act = p.flags & 0xffu;
+    const bool full = tile.m0 + kBM2 <= M && tile.n0 + kBN <= N && (uint64_t)M * N < (1ull << 30) &&
+                      !(p.flags & kMaskPositive);
+    if (full && (p.flags & kOutBf16)) {
+        if (act == 1) store_tile_full<1, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+        else if (act == 2) store_tile_full<2, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+        else store_tile_full<0, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+    } else if (full) {
+        if (act == 1) store_tile_full<1, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+        else if (act == 2) store_tile_full<2, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+        else store_tile_full<0, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+    } else if (act == 1) store_tile<1, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+    else if (act == 2) store_tile<2, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+    else store_tile<0, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+}
+
+
 bool tiled_shape_ok(const Problem &p) { return p.K != 0 && p.K % kBK == 0 && p.N % 8 == 0; }
 
 uint64_t tiled_tiles(const Problem &p)
@@ -253,25 +387,43 @@ uint64_t tiled_tiles(const Problem &p)
     return (uint64_t)((p.M + kBM - 1) / kBM) * ((p.N + kBN - 1) / kBN);
 }
 
-hipError_t launch_grouped_bf16_tiled(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches)
+// Jobs of at least this many rows take the 256-row tile (at most a quarter of
+// their last row tile is padding); smaller ones the 128-row tile.
+constexpr uint32_t kTiled256MinM = 192;
+
+template <int BM, typename Kernel>
+static hipError_t launch_tiled(Kernel kernel, int threads, const std::vector<Problem> &p, hipStream_t stream,
+                               uint64_t *launches)
 {
+    const uint32_t n = (uint32_t)p.size();
     for (uint32_t at = 0; at < n; at += kMaxProblems) {
         GroupArgs a{};
         a.n = std::min(kMaxProblems, n - at);
         uint64_t tiles = 0;
         for (uint32_t i = 0; i < a.n; ++i) {
             a.p[i] = p[at + i];
-            if (!tiled_shape_ok(a.p[i])) return hipErrorInvalidValue;
-            tiles += tiled_tiles(a.p[i]);
+            tiles += (uint64_t)((a.p[i].M + BM - 1) / BM) * ((a.p[i].N + kBN - 1) / kBN);
         }
         if (tiles == 0) continue;
         if (tiles > 0x7fffffffull) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(grouped_dense_bf16_tiled, dim3((uint32_t)tiles), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(kernel, dim3((uint32_t)tiles), dim3(threads), 0, stream, a);
         if (launches) *launches += 1;
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+hipError_t launch_grouped_bf16_tiled(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches)
+{
+    std::vector<Problem> big, small;
+    for (uint32_t i = 0; i < n; ++i) {
+        if (!tiled_shape_ok(p[i])) return hipErrorInvalidValue;
+        (p[i].M >= kTiled256MinM ? big : small).push_back(p[i]);
+    }
+    hipError_t e = launch_tiled<kBM2>(grouped_dense_bf16_tiled256, kThreads2, big, stream, launches);
+    if (e != hipSuccess) return e;
+    return launch_tiled<kBM>(grouped_dense_bf16_tiled, 256, small, stream, launches);
 }
 
 }  // namespace salus

@@ -160,10 +160,11 @@ def test_bf16_mixed_batch_sizes_and_depths_in_one_packed_iteration():
         assert e < TOL_BF16 and e < TOL_BF16_TIGHT, (j, e)
 
 
-@pytest.mark.parametrize("M", [128, 129, 200, 256, 300, 515])
+@pytest.mark.parametrize("M", [128, 129, 191, 192, 200, 256, 257, 300, 515, 770])
 def test_bf16_jobs_with_many_rows_take_the_tiled_kernel(M):
-    """M >= 128 and K a multiple of 64: LDS-tiled kernel (128 x 256 tiles), so these
-    shapes cover several tiles, ragged row and column tails and one-slab K."""
+    """M >= 128 and K a multiple of 64: LDS-tiled kernels (128 x 256 tiles; 256 x 256
+    from 192 rows), so these shapes cover several tiles, ragged row and column tails
+    and K of one, two, three and sixteen slabs."""
     shapes = [(64, 8, NONE), (192, 264, RELU), (128, 520, GELU), (1024, 256, NONE), (64, 1000, GELU)]
     jobs = [dict(M=M, dims=(K, N), acts=[act]) for K, N, act in shapes]
     jobs.append(dict(M=5, dims=(192, 264), acts=[GELU]))         # small job of the same round
@@ -179,7 +180,7 @@ def test_bf16_tiled_kernel_hidden_layers_round_to_bf16():
     jobs = [dict(M=m, dims=(256, 512, 320, 264), acts=[GELU, RELU, NONE]) for m in (128, 333, 600)]
     jobs.append(dict(M=7, dims=(256, 512, 320, 264), acts=[GELU, RELU, NONE]))
     outs, refs, launches = run_jobs(jobs, salus.BF16)
-    assert launches == 6                                          # tiled + streaming per layer depth
+    assert launches == 9                      # 128-row tiles, 256-row tiles and streaming per layer depth
     for o, r, j in zip(outs, refs, jobs):
         e = norm_rel_err(o, r)
         assert np.isfinite(o).all() and e < TOL_BF16 and e < TOL_BF16_TIGHT, (j, e)
