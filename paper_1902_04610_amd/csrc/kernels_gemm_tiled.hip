@@ -306,12 +306,15 @@ __global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled256(GroupAr
 #pragma unroll
         for (int r = 0; r < 4; ++r) wr[r] = *(const u32x4 *)(wsrc + (size_t)(k0 + r) * wpitch);
     };
-    auto store_slab = [&](uint32_t stage) {
+    auto store_x = [&](uint32_t stage) {
         unsigned char *base = smem + stage;
 #pragma unroll
         for (int i = 0; i < 4; ++i) *(u32x4 *)(base + xoff + 64 * i * kLine) = xr[i];
+    };
+    auto store_w = [&](uint32_t stage, int first) {      // columns first .. first+3 of the block
+        unsigned char *base = smem + stage;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = first; i < first + 4; ++i) {
             u32x2 b;       // column i of the block: dword j = (k 2j, k 2j+1)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
@@ -333,34 +336,52 @@ __global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled256(GroupAr
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    auto multiply = [&](const unsigned char *base, uint32_t ks) {
+        const uint32_t off = ((2u * ks + fh) ^ fs) << 4, off_odd = off ^ 64u;
+        bf16x8 av[2], bv[4];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) av[i] = *(const bf16x8 *)(base + afrag + 32 * i * kLine + (i & 1 ? off_odd : off));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bv[j] = *(const bf16x8 *)(base + bfrag + 32 * j * kLine + (j & 1 ? off_odd : off));
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+    };
+
+    // Slab s is multiplied out of one half of LDS while slab s+1 (already in
+    // registers) is written to the other half, a piece after each quarter of the
+    // multiplies so that the writes issue while the matrix pipe works through
+    // its queue, and slab s+2 is requested from memory.  The last slab has
+    // nothing to stage; the load past the end re-reads the last slab instead of
+    // branching.
     const uint32_t slabs = K / kBK;
     uint32_t cur = 0;
     load_slab(0);
-    store_slab(0);
-    if (slabs > 1) load_slab(kBK);
+    store_x(0);
+    store_w(0, 0);
+    store_w(0, 4);
+    load_slab(slabs > 1 ? kBK : 0);
     __syncthreads();
-    for (uint32_t s = 0; s < slabs; ++s) {
+    for (uint32_t s = 0; s + 1 < slabs; ++s) {
+        const unsigned char *base = smem + cur;
+        const uint32_t other = cur ^ kStageBytes;      // everyone left it at the last barrier
+        multiply(base, 0);
+        store_x(other);
+        multiply(base, 1);
+        store_w(other, 0);
+        multiply(base, 2);
+        store_w(other, 4);
+        multiply(base, 3);
+        load_slab((s + 2 < slabs ? s + 2 : slabs - 1) * kBK);
+        __syncthreads();
+        cur = other;
+    }
+    {
         const unsigned char *base = smem + cur;
 #pragma unroll
-        for (uint32_t ks = 0; ks < 4; ++ks) {
-            const uint32_t off = ((2u * ks + fh) ^ fs) << 4, off_odd = off ^ 64u;
-            bf16x8 av[2], bv[4];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) av[i] = *(const bf16x8 *)(base + afrag + 32 * i * kLine + (i & 1 ? off_odd : off));
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bv[j] = *(const bf16x8 *)(base + bfrag + 32 * j * kLine + (j & 1 ? off_odd : off));
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
-        }
-        if (s + 1 < slabs) {
-            store_slab(cur ^ kStageBytes);       // the other stage: everyone left it at the last barrier
-            if (s + 2 < slabs) load_slab((s + 2) * kBK);
-        }
-        __syncthreads();
-        cur ^= kStageBytes;
+        for (uint32_t ks = 0; ks < 4; ++ks) multiply(base, ks);
     }
 
     const uint32_t act = p.flags & 0xffu;
