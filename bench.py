@@ -393,7 +393,7 @@ def training_figures(torch, salus, stream, jobs=8, dims=(2048, 2048, 2048, 2048,
     return res
 
 
-def sweep_figures(torch, salus, stream, batches=(32, 48, 64, 96, 128, 256, 512, 1024, 2048, 4096)):
+def sweep_figures(torch, salus, stream, batches=(32, 48, 64, 80, 96, 112, 128, 256, 512, 1024, 2048, 4096)):
     """Supplemental, NOT the headline workload: the same 64 resident models with
     every model at M rows per round, M from the packing regime (weight stream
     bound) up to 4096 rows per model (compute bound), to show where the grouped

@@ -64,11 +64,11 @@ static hipError_t launch_groups(const Problem *p, uint32_t n, uint32_t tn, uint3
 
 // Rows per job from which the LDS-tiled kernel is used: always from 128 rows; from
 // 65 rows (where the streaming kernel needs a third row tile) if the jobs routed
-// there fill at least two waves of workgroups on 256 CUs.  Up to 64 rows the
+// there make up at least one workgroup per CU (256).  Up to 64 rows the
 // streaming kernel's two row tiles run side by side and the second one finds the
 // weights in L2, which measured faster than a half-empty 128-row tile.
 constexpr uint32_t kTiledAlways = 128, kTiledMaybe = 65;
-constexpr uint64_t kTiledMinGrid = 512;
+constexpr uint64_t kTiledMinGrid = 256;
 
 hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipStream_t stream,
                                uint64_t *launches)

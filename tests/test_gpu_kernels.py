@@ -187,7 +187,7 @@ def test_bf16_tiled_kernel_hidden_layers_round_to_bf16():
 
 
 def test_bf16_mid_sized_batches_go_tiled_when_the_round_fills_the_chip():
-    """65..127 rows: tiled only if the round's tiled jobs make up at least 512 workgroups."""
+    """65..127 rows: tiled only if the round's tiled jobs make up at least 256 workgroups."""
     jobs = [dict(M=[65, 80, 100, 127][i % 4], dims=(64, 2048), acts=[[NONE, RELU, GELU][i % 3]]) for i in range(64)]
     outs, refs, launches = run_jobs(jobs, salus.BF16)
     assert launches == 1
