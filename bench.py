@@ -264,7 +264,7 @@ def main():
         from oracle import dense
         dense.lib()
         cores = min(16, os.cpu_count() or 1)
-        sample_rounds = 4
+        sample_rounds = min(4, K_steps)
         work = []
         for r in range(W_steps, W_steps + sample_rounds):
             for m in range(MODELS):
