@@ -54,7 +54,7 @@ constexpr uint32_t kStripW = 1u << 10;      // W is stored in strips of 128 colu
 // One launch (or several when n > kMaxProblems): Y_g = act(X_g . W_g) for all g.
 hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipStream_t stream,
                                uint64_t *launches);
-// Jobs with many rows: LDS-tiled compute-bound kernel (128 x 256 tiles).
+// Jobs with many rows: LDS-tiled compute-bound kernel (128 x 256 tiles, 256 x 256 from 192 rows).
 // tiled_shape_ok says whether a problem may go there (K % 64 == 0, N % 8 == 0),
 // tiled_tiles how many workgroups it would occupy.
 bool tiled_shape_ok(const Problem &p);

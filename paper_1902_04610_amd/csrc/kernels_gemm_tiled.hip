@@ -1,21 +1,30 @@
 // Grouped dense layer for jobs that bring many rows (M >= 128, or more than 64
-// when the round holds enough of them to fill the chip with 128-row tiles): the
+// when the round holds enough of them to give every CU a tile): the
 // compute-bound counterpart of the weight-streaming kernel.  Same contract (one
 // launch runs one layer of every scheduled job, Salus paper, Section 3.3), but
-// here a weight is used by 128 rows per workgroup, so operands are staged
-// through LDS and every wavefront owns a 64 x 128 output block.
+// here a weight is used by 128 or 256 rows per workgroup, so operands are staged
+// through LDS.
 //
-// Workgroup tile 128 x 256, k-slab 64, four wavefronts (2 x 2), v_mfma_f32_32x32x16_bf16.
-//   HBM -> registers : 16-byte loads, issued one slab ahead of the multiply
-//   registers -> LDS : X rows as they are; W blocks of 8 k x 8 n are transposed in
+// Workgroup tile BM x 256 (BM = 256 for jobs from 192 rows, else 128), k-slab 64,
+// eight wavefronts (4 x 2 of 64 x 128, or 2 x 4 of 64 x 64), v_mfma_f32_32x32x16_bf16.
+//   HBM -> registers : 16-byte loads, issued two slabs ahead of the multiply
+//   registers -> LDS : X rows as they are; W blocks of 4 k x 8 n are transposed in
 //                      registers first, so that both operands sit in LDS as
 //                      [row or column][64 k-values] = 128 bytes per line
 //   LDS -> registers : one ds_read_b128 per 32x16 operand fragment
+// LDS holds two slabs: the slab after the one being multiplied is written while
+// it is multiplied - a quarter of the writes after each quarter of the MFMAs, so
+// that they issue while the matrix pipe works through its queue - and the one
+// after that is on its way from memory; one barrier per slab.  One workgroup
+// fills a CU (registers at BM = 256, LDS at BM = 128), so this overlap has to
+// come from inside it.  Per multiply-add the 256-row tile moves a third less
+// through L2 than the 128-row one ((256 + 256) / (256 * 256) against
+// (128 + 256) / (128 * 256) operand bytes).
 // The 16-byte slot of k-chunk c in line r is c ^ swz(r), swz(r) = (r ^ r/8) % 8.
 // Fragment reads touch 32 consecutive lines at one k-chunk, the transposed W
 // writes touch lines 8 apart at one k-chunk, X writes fill whole lines: with
 // this swizzle each of them spreads every 8 lanes that the LDS serves together
-// over all 8 slots of the 128-byte bank row.
+// over all 8 slots of the 128-byte bank row (measured: no bank conflicts).
 #include <algorithm>
 #include <vector>
 
@@ -134,153 +143,32 @@ __device__ inline void store_tile_full(const f32x16 (&acc)[FM][FN], const Proble
 
 // Requires K % 64 == 0 and N % 8 == 0 (the launcher routes other shapes to the
 // streaming kernel).  Rows >= M and columns >= N are loaded from clamped
-// addresses and never stored.
-__global__ __launch_bounds__(256, 2) void grouped_dense_bf16_tiled(GroupArgs a)
-{
-    __shared__ __attribute__((aligned(128))) unsigned char smem[(kBM + kBN) * kLine];
-    unsigned char *As = smem, *Bs = smem + kBM * kLine;
-    const Tile tile = find_tile_banded<kBM, kBN>(a);
-    const Problem &p = a.p[tile.problem];
-    const uint32_t M = p.M, K = p.K, N = p.N;
-    const uint32_t t = threadIdx.x, lane = t & 63u;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const uint32_t wm = wave >> 1, wn = wave & 1u;
-    const uint16_t *W = (const uint16_t *)p.W;
-    const uint16_t *X = (const uint16_t *)p.X;
-
-    // ---- HBM -> registers -> LDS assignment
-    // X: thread owns k-chunk ca of rows ra, ra+32, ra+64, ra+96
-    const uint32_t ca = t & 7u, ra = t >> 3;
-    const uint16_t *xsrc[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t row = tile.m0 + ra + 32u * i;
-        xsrc[i] = X + (size_t)(row < M ? row : M - 1) * K + 8u * ca;
-    }
-    const uint32_t xslot = ca ^ swz(ra);                 // line ra + 32*i: slot xslot ^ 4*(i%2)
-    // W: thread owns the 8 x 8 block (k-chunk kb, columns 8*nb .. 8*nb+7)
-    const uint32_t kb = lane >> 3, nb = (lane & 7u) + 8u * wave;
-    const uint32_t ncol = tile.n0 + 8u * nb, ncol_c = ncol < N ? ncol : 0u;
-    const bool strip = (p.flags & kStripW) != 0;      // W in contiguous K x 128 strips
-    const uint32_t wpitch = strip ? 128u : N;
-    const uint16_t *wsrc = strip ? W + (size_t)(ncol_c & ~127u) * K + (8u * kb) * 128u + (ncol_c & 127u)
-                                 : W + (size_t)(8u * kb) * N + ncol_c;
-
-    u32x4 xr[4], wr[8];
-    auto load_slab = [&](uint32_t k0) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) xr[i] = *(const u32x4 *)(xsrc[i] + k0);
-#pragma unroll
-        for (int r = 0; r < 8; ++r) wr[r] = *(const u32x4 *)(wsrc + (size_t)(k0 + r) * wpitch);
-    };
-    auto store_slab = [&]() {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *(u32x4 *)(As + (ra + 32 * i) * kLine + ((xslot ^ (4u * (i & 1))) << 4)) = xr[i];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            u32x4 b;   // column i of the block: dword j = (k 2j, k 2j+1)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                b[j] = __builtin_amdgcn_perm(wr[2 * j + 1][i >> 1], wr[2 * j][i >> 1],
-                                             (i & 1) ? 0x07060302u : 0x05040100u);
-            const uint32_t line = 8u * nb + i;
-            *(u32x4 *)(Bs + line * kLine + ((kb ^ swz(line)) << 4)) = b;
-        }
-    };
-
-    // ---- LDS -> MFMA operands: fragment line = base + (lane % 32), k-chunk 2*ks + lane/32
-    const uint32_t fl = lane & 31u, fh = lane >> 5, fs = swz(fl);
-    const unsigned char *afrag = As + (wm * 64u + fl) * kLine;
-    const unsigned char *bfrag = Bs + (wn * 128u + fl) * kLine;
-
-    f32x16 acc[2][4];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    const uint32_t slabs = K / kBK;
-    load_slab(0);
-    store_slab();
-    __syncthreads();
-    for (uint32_t s = 0; s < slabs; ++s) {
-        if (s + 1 < slabs) load_slab((s + 1) * kBK);
-#pragma unroll
-        for (uint32_t ks = 0; ks < 4; ++ks) {
-            // lines 32 apart differ in swz by 4: odd fragments use slot ^ 4
-            const uint32_t off = ((2u * ks + fh) ^ fs) << 4, off_odd = off ^ 64u;
-            bf16x8 av[2], bv[4];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) av[i] = *(const bf16x8 *)(afrag + 32 * i * kLine + (i & 1 ? off_odd : off));
-#pragma unroll
-            for (int j = 0; j < 4; ++j) bv[j] = *(const bf16x8 *)(bfrag + 32 * j * kLine + (j & 1 ? off_odd : off));
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
-        }
-        __syncthreads();                     // every wavefront has read this slab
-        if (s + 1 < slabs) {
-            store_slab();
-            __syncthreads();
-        }
-    }
-
-    // ---- epilogue: register r of a 32x32 block is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
-    const uint32_t act = p.flags & 0xffu;
-    const bool full = tile.m0 + kBM <= M && tile.n0 + kBN <= N && (uint64_t)M * N < (1ull << 30) &&
-                      !(p.flags & kMaskPositive);
-    if (full && (p.flags & kOutBf16)) {
-        if (act == 1) store_tile_full<1, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-        else if (act == 2) store_tile_full<2, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-        else store_tile_full<0, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-    } else if (full) {
-        if (act == 1) store_tile_full<1, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-        else if (act == 2) store_tile_full<2, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-        else store_tile_full<0, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-    } else if (act == 1) store_tile<1, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-    else if (act == 2) store_tile<2, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-    else store_tile<0, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-}
-
-
-// ---------------------------------------------------------------------------
-// The same scheme with a 256 x 256 tile and eight wavefronts (4 x 2, each again
-// 64 x 128), for jobs of at least 192 rows.  Per multiply-add it moves a third
-// less through L2 than the 128 x 256 tile ((256 + 256) / (256 * 256) against
-// (128 + 256) / (128 * 256) operand bytes), which is what bounds the smaller
-// tile: measured, its loads and LDS writes alone take as long as its MFMAs
-// alone.  One workgroup fills a CU's registers, so the overlap of memory and
-// MFMA phases has to come from inside it: LDS holds two slabs (128 KB), the slab
-// after the one being multiplied is written while it is multiplied, the one
-// after that is on its way from memory, and there is one barrier per slab.
-// A thread owns four 16-byte k-chunks of X (rows 64 apart) and a block of 4 k x 8
-// columns of W, which it transposes into eight 8-byte half-chunks.
-// ---------------------------------------------------------------------------
+// addresses and never stored.  A thread owns BM / 64 16-byte k-chunks of X (rows
+// 64 apart) and a block of 4 k x 8 columns of W, which it transposes into eight
+// 8-byte half-chunks.
 constexpr int kBM2 = 256, kThreads2 = 512;
-constexpr uint32_t kStageBytes = (kBM2 + kBN) * kLine;      // 64 KB
 
-__global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled256(GroupArgs a)
+// BM2 = 256: wavefronts 4 x 2, each 64 x 128.  BM2 = 128: 2 x 4, each 64 x 64.
+template <int BM2>
+__global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled(GroupArgs a)
 {
+    constexpr uint32_t kStageBytes = (BM2 + kBN) * kLine;      // 64 KB or 48 KB
+    constexpr int WN = BM2 == 256 ? 2 : 4, FN = kBN / (32 * WN), XR = BM2 / 64;
     __shared__ __attribute__((aligned(128))) unsigned char smem[2 * kStageBytes];
-    const Tile tile = find_tile_banded<kBM2, kBN>(a);
+    const Tile tile = find_tile_banded<BM2, kBN>(a);
     const Problem &p = a.p[tile.problem];
     const uint32_t M = p.M, K = p.K, N = p.N;
     const uint32_t t = threadIdx.x, lane = t & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const uint32_t wm = wave >> 1, wn = wave & 1u;
+    const uint32_t wm = wave / WN, wn = wave % WN;
     const uint16_t *W = (const uint16_t *)p.W;
     const uint16_t *X = (const uint16_t *)p.X;
 
-    // X: k-chunk ca of rows ra, ra+64, ra+128, ra+192 (lines 64 apart share their swizzle)
+    // X: k-chunk ca of rows ra, ra+64, ... (lines 64 apart share their swizzle)
     const uint32_t ca = t & 7u, ra = t >> 3;
-    const uint16_t *xsrc[4];
+    const uint16_t *xsrc[XR];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < XR; ++i) {
         const uint32_t row = tile.m0 + ra + 64u * i;
         xsrc[i] = X + (size_t)(row < M ? row : M - 1) * K + 8u * ca;
     }
@@ -296,20 +184,20 @@ __global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled256(GroupAr
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const uint32_t line = 8u * nb + i;
-        woff[i] = (kBM2 + line) * kLine + (((kq >> 1) ^ swz(line)) << 4) + 8u * (kq & 1u);
+        woff[i] = (BM2 + line) * kLine + (((kq >> 1) ^ swz(line)) << 4) + 8u * (kq & 1u);
     }
 
-    u32x4 xr[4], wr[4];
+    u32x4 xr[XR], wr[4];
     auto load_slab = [&](uint32_t k0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) xr[i] = *(const u32x4 *)(xsrc[i] + k0);
+        for (int i = 0; i < XR; ++i) xr[i] = *(const u32x4 *)(xsrc[i] + k0);
 #pragma unroll
         for (int r = 0; r < 4; ++r) wr[r] = *(const u32x4 *)(wsrc + (size_t)(k0 + r) * wpitch);
     };
     auto store_x = [&](uint32_t stage) {
         unsigned char *base = smem + stage;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *(u32x4 *)(base + xoff + 64 * i * kLine) = xr[i];
+        for (int i = 0; i < XR; ++i) *(u32x4 *)(base + xoff + 64 * i * kLine) = xr[i];
     };
     auto store_w = [&](uint32_t stage, int first) {      // columns first .. first+3 of the block
         unsigned char *base = smem + stage;
@@ -326,27 +214,27 @@ __global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled256(GroupAr
 
     const uint32_t fl = lane & 31u, fh = lane >> 5, fs = swz(fl);
     const uint32_t afrag = (wm * 64u + fl) * kLine;
-    const uint32_t bfrag = (kBM2 + wn * 128u + fl) * kLine;
+    const uint32_t bfrag = (BM2 + wn * (32u * FN) + fl) * kLine;
 
-    f32x16 acc[2][4];
+    f32x16 acc[2][FN];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     auto multiply = [&](const unsigned char *base, uint32_t ks) {
         const uint32_t off = ((2u * ks + fh) ^ fs) << 4, off_odd = off ^ 64u;
-        bf16x8 av[2], bv[4];
+        bf16x8 av[2], bv[FN];
 #pragma unroll
         for (int i = 0; i < 2; ++i) av[i] = *(const bf16x8 *)(base + afrag + 32 * i * kLine + (i & 1 ? off_odd : off));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) bv[j] = *(const bf16x8 *)(base + bfrag + 32 * j * kLine + (j & 1 ? off_odd : off));
+        for (int j = 0; j < FN; ++j) bv[j] = *(const bf16x8 *)(base + bfrag + 32 * j * kLine + (j & 1 ? off_odd : off));
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < FN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
     };
 
@@ -385,19 +273,19 @@ __global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled256(GroupAr
     }
 
     const uint32_t act = p.flags & 0xffu;
-    const bool full = tile.m0 + kBM2 <= M && tile.n0 + kBN <= N && (uint64_t)M * N < (1ull << 30) &&
+    const bool full = tile.m0 + BM2 <= M && tile.n0 + kBN <= N && (uint64_t)M * N < (1ull << 30) &&
                       !(p.flags & kMaskPositive);
     if (full && (p.flags & kOutBf16)) {
-        if (act == 1) store_tile_full<1, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-        else if (act == 2) store_tile_full<2, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-        else store_tile_full<0, true, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+        if (act == 1) store_tile_full<1, true, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+        else if (act == 2) store_tile_full<2, true, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+        else store_tile_full<0, true, 2, FN>(acc, p, tile, wm, wn, fl, fh);
     } else if (full) {
-        if (act == 1) store_tile_full<1, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-        else if (act == 2) store_tile_full<2, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-        else store_tile_full<0, false, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-    } else if (act == 1) store_tile<1, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-    else if (act == 2) store_tile<2, 2, 4>(acc, p, tile, wm, wn, fl, fh);
-    else store_tile<0, 2, 4>(acc, p, tile, wm, wn, fl, fh);
+        if (act == 1) store_tile_full<1, false, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+        else if (act == 2) store_tile_full<2, false, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+        else store_tile_full<0, false, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+    } else if (act == 1) store_tile<1, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+    else if (act == 2) store_tile<2, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+    else store_tile<0, 2, FN>(acc, p, tile, wm, wn, fl, fh);
 }
 
 
@@ -442,9 +330,9 @@ hipError_t launch_grouped_bf16_tiled(const Problem *p, uint32_t n, hipStream_t s
         if (!tiled_shape_ok(p[i])) return hipErrorInvalidValue;
         (p[i].M >= kTiled256MinM ? big : small).push_back(p[i]);
     }
-    hipError_t e = launch_tiled<kBM2>(grouped_dense_bf16_tiled256, kThreads2, big, stream, launches);
+    hipError_t e = launch_tiled<kBM2>(grouped_dense_bf16_tiled<kBM2>, kThreads2, big, stream, launches);
     if (e != hipSuccess) return e;
-    return launch_tiled<kBM>(grouped_dense_bf16_tiled, 256, small, stream, launches);
+    return launch_tiled<kBM>(grouped_dense_bf16_tiled<kBM>, kThreads2, small, stream, launches);
 }
 
 }  // namespace salus
