@@ -10,7 +10,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 struct GroupArgs {
     uint32_t n;
-    uint32_t pad;
+    uint32_t tiles;      // all tiles of the launch (kernels whose workgroups loop over tiles)
     Problem p[kMaxProblems];
 };
 

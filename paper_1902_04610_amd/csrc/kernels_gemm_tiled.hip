@@ -43,7 +43,7 @@ __device__ inline uint32_t swz(uint32_t line) { return (line ^ (line >> 3)) & 7u
 // Tiles of one job in bands of 8 row tiles, column tiles inside a band: the 64
 // tiles an XCD runs at a time then share 8 slabs of X and 8 slabs of W in its L2.
 template <int BM, int BN>
-__device__ inline Tile find_tile_banded(const GroupArgs &a)
+__device__ inline Tile find_tile_banded(const GroupArgs &a, uint32_t tile_id)
 {
     const int lane = threadIdx.x & 63;
     const bool valid = lane < (int)a.n;
@@ -53,7 +53,8 @@ __device__ inline Tile find_tile_banded(const GroupArgs &a)
         col_tiles = (a.p[lane].N + BN - 1) / BN;
     }
     const uint32_t first = wave_excl_scan_u32(row_tiles * col_tiles, nullptr);
-    const uint32_t id = xcd_remap(blockIdx.x, gridDim.x);
+    // the grid is a multiple of 8, so a workgroup's tiles all map to its own XCD's range
+    const uint32_t id = xcd_remap(tile_id, a.tiles);
     const int g = wave_find_range(first, id, valid);
     const uint32_t t = id - __shfl(first, g, 64);
     const uint32_t rt = __shfl(row_tiles, g, 64), ct = __shfl(col_tiles, g, 64);
@@ -149,37 +150,24 @@ __device__ inline void store_tile_full(const f32x16 (&acc)[FM][FN], const Proble
 constexpr int kBM2 = 256, kThreads2 = 512;
 
 // BM2 = 256: wavefronts 4 x 2, each 64 x 128.  BM2 = 128: 2 x 4, each 64 x 64.
+// The grid is one workgroup per CU; workgroup b runs tiles b, b + grid, ... and
+// requests the first slab of its next tile before the epilogue of the current
+// one, so that neither that latency nor a workgroup launch sits between tiles.
 template <int BM2>
 __global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled(GroupArgs a)
 {
     constexpr uint32_t kStageBytes = (BM2 + kBN) * kLine;      // 64 KB or 48 KB
     constexpr int WN = BM2 == 256 ? 2 : 4, FN = kBN / (32 * WN), XR = BM2 / 64;
     __shared__ __attribute__((aligned(128))) unsigned char smem[2 * kStageBytes];
-    const Tile tile = find_tile_banded<BM2, kBN>(a);
-    const Problem &p = a.p[tile.problem];
-    const uint32_t M = p.M, K = p.K, N = p.N;
     const uint32_t t = threadIdx.x, lane = t & 63u;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const uint32_t wm = wave / WN, wn = wave % WN;
-    const uint16_t *W = (const uint16_t *)p.W;
-    const uint16_t *X = (const uint16_t *)p.X;
 
     // X: k-chunk ca of rows ra, ra+64, ... (lines 64 apart share their swizzle)
     const uint32_t ca = t & 7u, ra = t >> 3;
-    const uint16_t *xsrc[XR];
-#pragma unroll
-    for (int i = 0; i < XR; ++i) {
-        const uint32_t row = tile.m0 + ra + 64u * i;
-        xsrc[i] = X + (size_t)(row < M ? row : M - 1) * K + 8u * ca;
-    }
     const uint32_t xoff = ra * kLine + ((ca ^ swz(ra)) << 4);
     // W: rows 4*kq .. 4*kq+3 of the slab, columns 8*nb .. 8*nb+7
     const uint32_t kq = (lane >> 3) + 8u * (wave >> 2), nb = (lane & 7u) + 8u * (wave & 3u);
-    const uint32_t ncol = tile.n0 + 8u * nb, ncol_c = ncol < N ? ncol : 0u;
-    const bool strip = (p.flags & kStripW) != 0;
-    const uint32_t wpitch = strip ? 128u : N;
-    const uint16_t *wsrc = strip ? W + (size_t)(ncol_c & ~127u) * K + (4u * kq) * 128u + (ncol_c & 127u)
-                                 : W + (size_t)(4u * kq) * N + ncol_c;
     uint32_t woff[8];      // byte offset of this thread's half-chunk in column line 8*nb + i
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -187,12 +175,38 @@ __global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled(GroupArgs 
         woff[i] = (BM2 + line) * kLine + (((kq >> 1) ^ swz(line)) << 4) + 8u * (kq & 1u);
     }
 
+    struct Source {           // where this thread's part of a tile's operands comes from
+        Tile tile;
+        const uint16_t *x[XR];
+        const uint16_t *w;
+        uint32_t wpitch;
+    };
+    auto locate = [&](uint32_t id) {
+        Source src;
+        src.tile = find_tile_banded<BM2, kBN>(a, id);
+        const Problem &p = a.p[src.tile.problem];
+        const uint32_t M = p.M, K = p.K, N = p.N;
+        const uint16_t *W = (const uint16_t *)p.W;
+        const uint16_t *X = (const uint16_t *)p.X;
+#pragma unroll
+        for (int i = 0; i < XR; ++i) {
+            const uint32_t row = src.tile.m0 + ra + 64u * i;
+            src.x[i] = X + (size_t)(row < M ? row : M - 1) * K + 8u * ca;
+        }
+        const uint32_t ncol = src.tile.n0 + 8u * nb, ncol_c = ncol < N ? ncol : 0u;
+        const bool strip = (p.flags & kStripW) != 0;
+        src.wpitch = strip ? 128u : N;
+        src.w = strip ? W + (size_t)(ncol_c & ~127u) * K + (4u * kq) * 128u + (ncol_c & 127u)
+                      : W + (size_t)(4u * kq) * N + ncol_c;
+        return src;
+    };
+
     u32x4 xr[XR], wr[4];
-    auto load_slab = [&](uint32_t k0) {
+    auto load_slab = [&](const Source &src, uint32_t k0) {
 #pragma unroll
-        for (int i = 0; i < XR; ++i) xr[i] = *(const u32x4 *)(xsrc[i] + k0);
+        for (int i = 0; i < XR; ++i) xr[i] = *(const u32x4 *)(src.x[i] + k0);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) wr[r] = *(const u32x4 *)(wsrc + (size_t)(k0 + r) * wpitch);
+        for (int r = 0; r < 4; ++r) wr[r] = *(const u32x4 *)(src.w + (size_t)(k0 + r) * src.wpitch);
     };
     auto store_x = [&](uint32_t stage) {
         unsigned char *base = smem + stage;
@@ -217,13 +231,6 @@ __global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled(GroupArgs 
     const uint32_t bfrag = (BM2 + wn * (32u * FN) + fl) * kLine;
 
     f32x16 acc[2][FN];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
     auto multiply = [&](const unsigned char *base, uint32_t ks) {
         const uint32_t off = ((2u * ks + fh) ^ fs) << 4, off_odd = off ^ 64u;
         bf16x8 av[2], bv[FN];
@@ -238,56 +245,80 @@ __global__ __launch_bounds__(kThreads2) void grouped_dense_bf16_tiled(GroupArgs 
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
     };
 
-    // Slab s is multiplied out of one half of LDS while slab s+1 (already in
-    // registers) is written to the other half, a piece after each quarter of the
-    // multiplies so that the writes issue while the matrix pipe works through
-    // its queue, and slab s+2 is requested from memory.  The last slab has
-    // nothing to stage; the load past the end re-reads the last slab instead of
-    // branching.
-    const uint32_t slabs = K / kBK;
-    uint32_t cur = 0;
-    load_slab(0);
-    store_x(0);
-    store_w(0, 0);
-    store_w(0, 4);
-    load_slab(slabs > 1 ? kBK : 0);
-    __syncthreads();
-    for (uint32_t s = 0; s + 1 < slabs; ++s) {
-        const unsigned char *base = smem + cur;
-        const uint32_t other = cur ^ kStageBytes;      // everyone left it at the last barrier
-        multiply(base, 0);
-        store_x(other);
-        multiply(base, 1);
-        store_w(other, 0);
-        multiply(base, 2);
-        store_w(other, 4);
-        multiply(base, 3);
-        load_slab((s + 2 < slabs ? s + 2 : slabs - 1) * kBK);
-        __syncthreads();
-        cur = other;
-    }
-    {
-        const unsigned char *base = smem + cur;
+    const uint32_t tiles = a.tiles;
+    uint32_t id = blockIdx.x;
+    Source src = locate(id);
+    load_slab(src, 0);
+    for (;;) {
+        const Problem &p = a.p[src.tile.problem];
+        const uint32_t M = p.M, N = p.N, slabs = p.K / kBK;
 #pragma unroll
-        for (uint32_t ks = 0; ks < 4; ++ks) multiply(base, ks);
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        // Slab s is multiplied out of one half of LDS while slab s+1 (already in
+        // registers) is written to the other half, a piece after each quarter of the
+        // multiplies so that the writes issue while the matrix pipe works through
+        // its queue, and slab s+2 is requested from memory.  The last slab has
+        // nothing to stage; the load past the end re-reads the last slab instead of
+        // branching.
+        uint32_t stage = 0;
+        __syncthreads();                     // the previous tile's last slab has been read
+        store_x(0);
+        store_w(0, 0);
+        store_w(0, 4);
+        load_slab(src, slabs > 1 ? kBK : 0);
+        __syncthreads();
+        for (uint32_t s = 0; s + 1 < slabs; ++s) {
+            const unsigned char *base = smem + stage;
+            const uint32_t other = stage ^ kStageBytes;      // everyone left it at the last barrier
+            multiply(base, 0);
+            store_x(other);
+            multiply(base, 1);
+            store_w(other, 0);
+            multiply(base, 2);
+            store_w(other, 4);
+            multiply(base, 3);
+            load_slab(src, (s + 2 < slabs ? s + 2 : slabs - 1) * kBK);
+            __syncthreads();
+            stage = other;
+        }
+        {
+            const unsigned char *base = smem + stage;
+#pragma unroll
+            for (uint32_t ks = 0; ks < 4; ++ks) multiply(base, ks);
+        }
+
+        // the next tile's first slab travels while this tile's epilogue runs
+        const Tile tile = src.tile;
+        const uint32_t next = id + gridDim.x;
+        const bool more = next < tiles;
+        if (more) {
+            src = locate(next);
+            load_slab(src, 0);
+        }
+
+        const uint32_t act = p.flags & 0xffu;
+        const bool full = tile.m0 + BM2 <= M && tile.n0 + kBN <= N && (uint64_t)M * N < (1ull << 30) &&
+                          !(p.flags & kMaskPositive);
+        if (full && (p.flags & kOutBf16)) {
+            if (act == 1) store_tile_full<1, true, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+            else if (act == 2) store_tile_full<2, true, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+            else store_tile_full<0, true, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+        } else if (full) {
+            if (act == 1) store_tile_full<1, false, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+            else if (act == 2) store_tile_full<2, false, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+            else store_tile_full<0, false, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+        } else if (act == 1) store_tile<1, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+        else if (act == 2) store_tile<2, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+        else store_tile<0, 2, FN>(acc, p, tile, wm, wn, fl, fh);
+        if (!more) break;
+        id = next;
     }
-
-    const uint32_t act = p.flags & 0xffu;
-    const bool full = tile.m0 + BM2 <= M && tile.n0 + kBN <= N && (uint64_t)M * N < (1ull << 30) &&
-                      !(p.flags & kMaskPositive);
-    if (full && (p.flags & kOutBf16)) {
-        if (act == 1) store_tile_full<1, true, 2, FN>(acc, p, tile, wm, wn, fl, fh);
-        else if (act == 2) store_tile_full<2, true, 2, FN>(acc, p, tile, wm, wn, fl, fh);
-        else store_tile_full<0, true, 2, FN>(acc, p, tile, wm, wn, fl, fh);
-    } else if (full) {
-        if (act == 1) store_tile_full<1, false, 2, FN>(acc, p, tile, wm, wn, fl, fh);
-        else if (act == 2) store_tile_full<2, false, 2, FN>(acc, p, tile, wm, wn, fl, fh);
-        else store_tile_full<0, false, 2, FN>(acc, p, tile, wm, wn, fl, fh);
-    } else if (act == 1) store_tile<1, 2, FN>(acc, p, tile, wm, wn, fl, fh);
-    else if (act == 2) store_tile<2, 2, FN>(acc, p, tile, wm, wn, fl, fh);
-    else store_tile<0, 2, FN>(acc, p, tile, wm, wn, fl, fh);
 }
-
 
 bool tiled_shape_ok(const Problem &p) { return p.K != 0 && p.K % kBK == 0 && p.N % 8 == 0; }
 
@@ -299,6 +330,18 @@ uint64_t tiled_tiles(const Problem &p)
 // Jobs of at least this many rows take the 256-row tile (at most a quarter of
 // their last row tile is padding); smaller ones the 128-row tile.
 constexpr uint32_t kTiled256MinM = 192;
+
+static uint32_t resident_grid()
+{
+    static uint32_t cached = 0;
+    if (cached) return cached;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8)
+        cus = 256;
+    cached = (uint32_t)cus & ~7u;
+    return cached;
+}
 
 template <int BM, typename Kernel>
 static hipError_t launch_tiled(Kernel kernel, int threads, const std::vector<Problem> &p, hipStream_t stream,
@@ -315,7 +358,11 @@ static hipError_t launch_tiled(Kernel kernel, int threads, const std::vector<Pro
         }
         if (tiles == 0) continue;
         if (tiles > 0x7fffffffull) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(kernel, dim3((uint32_t)tiles), dim3(threads), 0, stream, a);
+        a.tiles = (uint32_t)tiles;
+        // one workgroup per CU (it fills the CU); a multiple of 8 so that the
+        // workgroups of an XCD keep to that XCD's range of tiles
+        const uint32_t grid = (uint32_t)std::min<uint64_t>(tiles, resident_grid());
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, stream, a);
         if (launches) *launches += 1;
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
