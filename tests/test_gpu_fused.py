@@ -175,3 +175,53 @@ def test_a_wait_that_gives_up_is_reported_and_the_pool_stays_usable():
     for o, ref in zip(outs, refs):
         assert norm_rel_err(o, ref) < TOL_BF16_TIGHT
     fleet.dp.close()
+
+
+def run_mixed_dtypes(fuse):
+    """Float and bf16 jobs of different depths in ONE packed iteration."""
+    specs = [(salus.F32, 6, (64, 100, 36)), (salus.BF16, 9, (128, 136, 72, 40)), (salus.F32, 20, (40, 12)),
+             (salus.BF16, 32, (256, 264))]
+    acts_of = lambda dims: [RELU] * (len(dims) - 2) + [NONE]
+    layouts = [mlp_layout(d, 4 if dt == salus.F32 else 2, m) for dt, m, d in specs]
+    cap = (sum(l[1] + l[5] for l in layouts) + 4096 + 255) // 256 * 256
+    dp = DevicePool(cap, policy=salus.POLICY_PACK, fuse_depths=fuse)
+    rng = np.random.default_rng(31)
+    items, refs = [], []
+    for (dt, M, dims), (w_offs, P, x_off, y_off, h_off, E) in zip(specs, layouts):
+        st, jid = dp.pool.lane_alloc(P, E, 0, 0)
+        assert st == salus.OK
+        q = dp.pool.job_query(jid)
+        Ws = [(rng.standard_normal((K, N)) / np.sqrt(K)).astype(np.float32) for K, N in zip(dims[:-1], dims[1:])]
+        X = rng.uniform(-1, 1, (M, dims[0])).astype(np.float32)
+        if dt == salus.BF16:
+            Ws, X = [synth.f32_to_bf16_bits(w) for w in Ws], synth.f32_to_bf16_bits(X)
+        for w, off in zip(Ws, w_offs):
+            dp.write(q.persist_off + off, w)
+        dp.write(q.lane_off + x_off, X)
+        dp.write(q.lane_off + y_off, np.full((M, dims[-1]), np.nan, np.float32))
+        acts = acts_of(dims)
+        items.append(dict(job=jid, M=M, dtype=dt, x_off=x_off, y_off=y_off, h_off=h_off,
+                          layers=[(K, N, off, a) for K, N, off, a in zip(dims[:-1], dims[1:], w_offs, acts)]))
+        fwd = dense.mlp_forward_f32 if dt == salus.F32 else dense.mlp_forward_bf16
+        refs.append(fwd(X, Ws, acts)[-1])
+    descs, keep = salus.Pool.make_descs(items)
+    assert dp.pool.grouped_forward(descs, stream=dp.stream) == salus.OK
+    dp.sync()
+    assert dp.pool.fused_check() == salus.OK
+    outs = []
+    for it, (dt, M, dims) in zip(items, specs):
+        q = dp.pool.job_query(it["job"])
+        outs.append(dp.read(q.lane_off + it["y_off"], M * dims[-1] * 4, np.float32).reshape(M, dims[-1]).copy())
+    launches = dp.pool.stats()["gemm_launches"]
+    dp.close()
+    return outs, refs, launches, [dt for dt, _, _ in specs]
+
+
+def test_float_and_bf16_jobs_in_one_round_both_ways():
+    fused, refs, fused_launches, dts = run_mixed_dtypes(True)
+    plain, _, plain_launches, _ = run_mixed_dtypes(False)
+    assert fused_launches == 2                 # one launch per dtype
+    assert plain_launches == 2 + 3             # float jobs: 2 depths, bf16 jobs: 3
+    for f, p, r, dt in zip(fused, plain, refs, dts):
+        assert np.array_equal(f.view(np.uint32), p.view(np.uint32))
+        assert norm_rel_err(f, r) < (TOL_F32 if dt == salus.F32 else TOL_BF16_TIGHT)
