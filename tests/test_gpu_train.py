@@ -146,7 +146,7 @@ def check_step(job, Xb, labels, step, tol_grad=TOL_GRAD):
     job.Wm, job.Wb = gWm, gWb
 
 
-def run(configs, steps, seed, update_launches=1):
+def run(configs, steps, seed, update_launches=1, extra_forward_launches=0):
     rng = np.random.default_rng(seed)
     cap = 0
     specs = []
@@ -174,7 +174,7 @@ def run(configs, steps, seed, update_launches=1):
         dp.sync()
         depth = max(len(j.layers) for j in jobs)
         # forward + loss + input gradients + ONE update launch for all layers, shared by all jobs
-        assert dp.pool.stats()["gemm_launches"] - before == depth + 1 + (depth - 1) + update_launches
+        assert dp.pool.stats()["gemm_launches"] - before == depth + extra_forward_launches + 1 + (depth - 1) + update_launches
         for j, (Xb, labels) in zip(jobs, batches):
             check_step(j, Xb, labels, step)
     dp.close()
@@ -188,6 +188,12 @@ def test_train_step_ragged_shapes():
 def test_more_update_problems_than_one_launch_holds():
     # 24 jobs x 3 layers = 72 (job, layer) updates: two update launches of at most 64
     run([((40, 72, 48, 16), 1 + k % 9, 0.03) for k in range(24)], steps=1, seed=8, update_launches=2)
+
+
+def test_training_jobs_with_many_rows_use_the_tiled_forward():
+    # 200 and 130 rows with widths that are multiples of 64: the forward layers take the
+    # LDS-tiled kernel (one launch per tile height), the input gradients the streaming one
+    run([((128, 256, 64), 200, 0.02), ((64, 128, 64), 130, 0.05)], steps=2, seed=9, extra_forward_launches=2)
 
 
 def test_train_step_loss_kernel_paths():
