@@ -55,7 +55,9 @@ enum {
 /* Scheduling policies of Section 4. */
 enum {
     SALUS_POLICY_FIFO = 0,     /* oldest runnable job of the pool only */
-    SALUS_POLICY_FAIR = 1,     /* per lane: least attained service (round-robin) */
+    SALUS_POLICY_FAIR = 1,     /* per lane: least attained service (round-robin); a job enters a
+                                  lane level with the least-served job it competes with, so
+                                  shares become 1/n at once (Sections 4.3 and 5.1.2) */
     SALUS_POLICY_PRIORITY = 2, /* per lane: highest priority, then shortest remaining (SRTF) */
     SALUS_POLICY_PACK = 3      /* every lane runs its oldest runnable job */
 };
@@ -102,7 +104,7 @@ typedef struct {
     uint64_t pending;      /* iterations still to run */
     uint64_t served;       /* iterations issued so far */
     uint64_t cost;         /* duration of one iteration in the caller's time unit (default 1) */
-    uint64_t attained;     /* sum of the costs of the iterations issued so far */
+    uint64_t attained;     /* service level the job entered its lane at + the costs of its iterations since */
     uint64_t arrival_round, admit_round;   /* admit_round = UINT64_MAX while queued */
 } salus_job_info;
 

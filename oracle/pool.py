@@ -235,11 +235,28 @@ class Pool:
             self.events.append((EV_LANE_GROW, lane.id, lane.size))
         lane.ref += 1
         job.lane = lane.id
+        job.attained = self.lane_service_level(lane.id, job)
         self.place_persistent(job, self.floor())
         job.state = RESIDENT
         job.admit_round = self.round
         self.stats['admitted'] += 1
         self.events.append((EV_ADMIT, job.id, lane.id))
+
+    def lane_service_level(self, lane_id, newcomer):
+        """Attained service a job starts with when it enters a lane.  Section 4.3
+        equalizes total service over time inside a lane; Section 5.1.2 (fair
+        sharing microbenchmark) says that when a further job starts every
+        job's share drops to 1/n at once.  A newcomer that started at zero
+        would instead receive every iteration until it had caught up with jobs
+        that ran before it existed.  Reading taken: service is equalized from
+        the moment a job joins, i.e. it starts level with the least-served job
+        it competes with - the lane's runnable jobs, or, when none is runnable
+        at that moment, the lane's resident jobs; zero in an empty lane."""
+        others = [j for j in self.jobs
+                  if j is not newcomer and j.state == RESIDENT and j.lane == lane_id]
+        runnable = [j for j in others if j.pending > 0 and not j.held]
+        level = runnable or others
+        return min((j.attained for j in level), default=0)
 
     def process_requests(self):
         """ProcessRequests of Algorithm 1: every queued request is tried in
@@ -419,7 +436,8 @@ class Pool:
         pending.  Returns [(job id, lane id)] in lane creation order.
 
         FAIR/RR  - least attained service (sum of the costs of the iterations
-                   issued so far); tie: oldest job.
+                   issued since the job joined the lane, plus the level it
+                   joined at, see lane_service_level); tie: oldest job.
         PRIORITY - highest priority, then shortest remaining time (pending
                    iterations x cost), then oldest (SRTF when priorities are
                    equal; preemption at round boundaries).

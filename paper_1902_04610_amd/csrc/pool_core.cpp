@@ -160,6 +160,7 @@ int PoolCore::admit(Job &j, Choice c)
     Lane &l = lanes_[c.index];
     l.ref += 1;
     j.lane = l.id;
+    j.attained = entry_level(j);
     if (int rc = place(j, floor())) return rc;
     j.state = SALUS_JOB_RESIDENT;
     sumP_ += j.P;
@@ -167,6 +168,22 @@ int PoolCore::admit(Job &j, Choice c)
     stats.admitted += 1;
     log(SALUS_EV_ADMIT, j.id, l.id);
     return SALUS_OK;
+}
+
+// FAIR (Section 4.3) equalizes service inside a lane; the fair-sharing run of
+// Section 5.1.2 shows every job's share dropping to 1/n as soon as a further job
+// starts.  A job therefore enters its lane level with the least-served job it
+// competes with (runnable jobs first, else resident ones), not at zero: starting
+// at zero would hand it every iteration until it had caught up.
+uint64_t PoolCore::entry_level(const Job &j) const
+{
+    uint64_t lo[2] = {UINT64_MAX, UINT64_MAX};      // [0] runnable, [1] resident
+    for (const Job &o : jobs_) {
+        if (o.id == j.id || o.state != SALUS_JOB_RESIDENT || o.lane != j.lane) continue;
+        lo[1] = std::min(lo[1], o.attained);
+        if (o.pending > 0 && !o.held) lo[0] = std::min(lo[0], o.attained);
+    }
+    return lo[0] != UINT64_MAX ? lo[0] : lo[1] != UINT64_MAX ? lo[1] : 0;
 }
 
 int PoolCore::host_buffer(Job &j, void *pinned)

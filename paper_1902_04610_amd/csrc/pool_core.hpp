@@ -93,6 +93,7 @@ private:
     Choice find_lane(uint64_t P, uint64_t E, uint64_t residentP) const;
     void process_requests();
     int admit(Job &j, Choice c);
+    uint64_t entry_level(const Job &j) const;
     int place(Job &j, uint64_t fl);
     bool first_fit(uint64_t P, uint64_t fl, uint64_t *off) const;
     int evict(Job &j, bool automatic, void *pinned, bool copied = false);

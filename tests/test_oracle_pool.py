@@ -355,32 +355,73 @@ def test_priority_eviction_is_skipped_when_it_cannot_help():
 # ------------------------------------------------------------------ scheduling
 def test_fair_share_follows_arrivals_and_departures():
     """Section 5.1.2, fair sharing: with n equal jobs in one lane each gets 1/n of
-    the iterations, and the share changes right when a job arrives or leaves."""
+    the iterations, and the share changes right when a job arrives or leaves.
+    Only the public calls are used: the oracle's state is never edited."""
     p = op.Pool(1000, granule=1, max_lanes=1, policy=op.RR)
-    ran = []
 
     def run(rounds):
         out = []
         for _ in range(rounds):
             (j, _), = p.schedule_iteration()
             out.append(j)
-        ran.extend(out)
         return out
     a = p.job_arrive(10, 100, 0, 10 ** 6)[1]
-    assert run(6) == [a] * 6
+    assert run(6) == [a] * 6                                  # share 1
     b = p.job_arrive(10, 100, 0, 10 ** 6)[1]
-    p.jobs[b].attained = p.jobs[a].attained   # a newcomer starts level with the lane (no catch-up burst)
     got = run(6)
-    assert got.count(a) == 3 and got.count(b) == 3
+    assert got.count(a) == 3 and got.count(b) == 3            # halved at once, not after a catch-up burst
+    assert set(got[:2]) == {a, b}                             # ... within the very first two rounds
     c = p.job_arrive(10, 100, 0, 10 ** 6)[1]
-    p.jobs[c].attained = p.jobs[a].attained
     got = run(9)
-    assert [got.count(x) for x in (a, b, c)] == [3, 3, 3]
+    assert [got.count(x) for x in (a, b, c)] == [3, 3, 3]     # a third each
+    assert set(got[:3]) == {a, b, c}
     p.job_finish(c)
     got = run(6)
-    assert got.count(a) == 3 and got.count(b) == 3
+    assert got.count(a) == 3 and got.count(b) == 3            # the reverse when jobs leave
     p.job_finish(b)
     assert run(4) == [a] * 4
+
+
+def test_fair_newcomer_starts_level_with_the_jobs_it_competes_with():
+    """Reading of Section 4.3 against Section 5.1.2: a job that enters a lane
+    starts at the least attained service among the lane's runnable jobs (not at
+    zero), else among its resident jobs; zero in an empty lane."""
+    p = op.Pool(1000, granule=1, max_lanes=1, policy=op.RR)
+    a = p.job_arrive(10, 100, 0, 100)[1]
+    b = p.job_arrive(10, 100, 0, 100)[1]
+    for _ in range(10):
+        p.schedule_iteration()
+    assert (p.jobs[a].attained, p.jobs[b].attained) == (5, 5)
+    p.set_pending(b, 0)                       # b idles; a runs alone
+    for _ in range(4):
+        p.schedule_iteration()
+    assert (p.jobs[a].attained, p.jobs[b].attained) == (9, 5)
+    c = p.job_arrive(10, 100, 0, 100)[1]      # competes with a only: starts at 9, not at b's 5
+    assert p.jobs[c].attained == 9 and p.jobs[c].served == 0
+    p.set_pending(a, 0)
+    d = p.job_arrive(10, 100, 0, 100)[1]      # runnable: c (9) -> 9
+    assert p.jobs[d].attained == 9
+    p.set_pending(c, 0), p.set_pending(d, 0)
+    e = p.job_arrive(10, 100, 0, 100)[1]      # nobody runnable: least among the resident jobs
+    assert p.jobs[e].attained == 5
+    # costs: the level is in the same unit as the service it is compared with
+    q = op.Pool(1000, granule=1, max_lanes=1, policy=op.RR)
+    x = q.job_arrive(10, 100, 0, 100)[1]
+    q.set_cost(x, 7)
+    for _ in range(3):
+        q.schedule_iteration()
+    y = q.job_arrive(10, 100, 0, 100)[1]
+    assert q.jobs[y].attained == 21
+    # a queued job gets its level when it is admitted, not when it arrives
+    r = op.Pool(100, granule=1, max_lanes=1, policy=op.RR)
+    u = r.job_arrive(40, 10, 0, 100)[1]
+    v = r.job_arrive(40, 10, 0, 100)[1]
+    w = r.job_arrive(40, 10, 0, 100)[1]
+    assert r.jobs[w].state == op.QUEUED
+    for _ in range(6):
+        r.schedule_iteration()
+    r.job_finish(u)
+    assert r.jobs[w].state == op.RESIDENT and r.jobs[w].attained == r.jobs[v].attained == 3
 
 
 def test_fair_strict_rotation_for_equal_jobs():
