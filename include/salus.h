@@ -96,11 +96,11 @@ typedef struct {
     int32_t  priority;
     int32_t  auto_evicted; /* 1 if priority admission evicted it (it is restored automatically) */
     int32_t  in_transit;   /* 1 between salus_switch_*_begin and _end: resident but not runnable */
-    int32_t  reserved;
+    int32_t  lane_parked;  /* 1 while no job of the lane is resident: the lane then holds no bytes */
     uint64_t P, E;         /* granule-rounded sizes */
     uint64_t persist_off;  /* valid while RESIDENT; changes on compact / switch_in */
     uint64_t lane_off;     /* current base of the job's lane; changes when older lanes vanish or grow */
-    uint64_t lane_size;    /* L_j */
+    uint64_t lane_size;    /* L_j (reserved at lane_off unless lane_parked) */
     uint64_t pending;      /* iterations still to run */
     uint64_t served;       /* iterations issued so far */
     uint64_t cost;         /* duration of one iteration in the caller's time unit (default 1) */
@@ -161,7 +161,7 @@ typedef struct {
 
 enum { SALUS_EV_ADMIT = 0, SALUS_EV_EVICT = 1, SALUS_EV_RESTORE = 2, SALUS_EV_LANE_NEW = 3,
        SALUS_EV_LANE_GROW = 4, SALUS_EV_LANE_DEL = 5, SALUS_EV_LANE_MOVED = 6, SALUS_EV_COMPACT = 7,
-       SALUS_EV_LANE_SHRINK = 8 };
+       SALUS_EV_LANE_SHRINK = 8, SALUS_EV_LANE_PARK = 9, SALUS_EV_LANE_UNPARK = 10 };
 
 /* kind ADMIT: a = job, b = lane | EVICT: a = job, b = bytes | RESTORE: a = job,
  * b = new persistent offset | LANE_NEW / LANE_GROW / LANE_SHRINK: a = lane, b = size |
@@ -248,7 +248,11 @@ int32_t salus_schedule_iteration(salus_pool_t *pool, salus_slot *out, uint32_t c
 int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
                               void *stream);
 
-/* After the caller has synchronized the stream: SALUS_OK if every device-side
+/* MANDATORY after fused launches, before their outputs are used: the device-side
+ * wait relies on workgroups being dispatched in index order, which the hardware
+ * does today but no specification promises; when that fails the launch still
+ * ends (the wait is bounded) and this call is the only place that says so.
+ * After the caller has synchronized the stream: SALUS_OK if every device-side
  * wait of the fused launches completed since the last check ended normally,
  * SALUS_ETIMEOUT if one gave up (the outputs of those launches are invalid; the
  * pool stays usable).  A wait gives up after `polls` polls of about a
@@ -327,22 +331,34 @@ int32_t salus_switch_in(salus_pool_t *pool, int32_t job);
  *              back is ordered after all work already on the pool's stream.
  *   in_end:    as out_end; afterwards the job is runnable.
  * A compaction that runs while transfers are in flight is ordered after them
- * on the device.  A pool without device memory only does the bookkeeping. */
+ * on the device.  A pool without device memory only does the bookkeeping.
+ * If the HIP runtime reports a failed transfer, _end returns SALUS_EHIP on every
+ * call and the job stays in transit; salus_lane_free then gives the job up. */
 int32_t salus_switch_out_begin(salus_pool_t *pool, int32_t job, void *pinned_or_null, void *copy_stream);
 int32_t salus_switch_out_end(salus_pool_t *pool, int32_t job, int32_t wait);
 int32_t salus_switch_in_begin(salus_pool_t *pool, int32_t job, void *copy_stream);
 int32_t salus_switch_in_end(salus_pool_t *pool, int32_t job, int32_t wait);
 
-/* Slide all live persistent blocks to the low end in address order; new offset
- * = exclusive prefix sum of the granule-rounded sizes.  Executes the moves on
- * the device (overlap-safe) and writes the plan to plan_out[0..*n_moves)
- * (at most cap entries are written; *n_moves is the full count). */
+/* Defragmentation of the persistent region.  The paper is silent here: Section
+ * 3.3.1 only removes fragmentation between lanes (for free, since ephemeral
+ * memory is dead between iterations) and calls the classical move-out /
+ * move-back scheme costly; it never moves persistent memory and does not say
+ * how that region is allocated.  Reading taken: slide all live persistent
+ * blocks to the low end in address order; new offset = exclusive prefix sum of
+ * the granule-rounded sizes.  Executes the moves on the device (overlap-safe;
+ * staging, if any, only in the unused gap between the highest live block and
+ * the lanes, so lane contents survive) and writes the plan to
+ * plan_out[0..*n_moves) in ascending source order (at most cap entries are
+ * written; *n_moves is the full count).  Blocks that already sit at their
+ * final offset do not appear.  lane_alloc, switch_in and switch_in_begin run the
+ * same compaction by themselves when a request needs it. */
 int32_t salus_compact(salus_pool_t *pool, salus_move *plan_out, uint32_t cap, uint32_t *n_moves);
 
 int32_t salus_get_stats(salus_pool_t *pool, salus_stats *out);
 /* Copies and clears the event log (at most cap entries; *n = entries copied). */
 int32_t salus_poll_events(salus_pool_t *pool, salus_event *out, uint32_t cap, uint32_t *n);
-/* Lane ids in creation order with their current base and size. */
+/* Lane ids in creation order with their current base and the bytes they hold
+ * (L_j; 0 for a parked lane, i.e. one whose jobs are all evicted). */
 int32_t salus_lanes(salus_pool_t *pool, int32_t *ids, uint64_t *offs, uint64_t *sizes,
                     uint32_t cap, uint32_t *n);
 const char *salus_last_error(salus_pool_t *pool);

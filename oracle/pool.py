@@ -36,7 +36,7 @@ EINVAL, ENOMEM, ENOTRESIDENT, EBUSY, ENEVER = -1, -2, -3, -4, -5
 
 # event kinds, in the order they are appended to Pool.events
 EV_ADMIT, EV_EVICT, EV_RESTORE, EV_LANE_NEW, EV_LANE_GROW, EV_LANE_DEL, \
-    EV_LANE_MOVED, EV_COMPACT, EV_LANE_SHRINK = range(9)
+    EV_LANE_MOVED, EV_COMPACT, EV_LANE_SHRINK, EV_LANE_PARK, EV_LANE_UNPARK = range(11)
 
 
 def round_up(x, a):
@@ -91,8 +91,22 @@ class Pool:
                           restores=0, admitted=0)
 
     # ---------------------------------------------------------------- layout
-    def sum_L(self):
-        return sum(l.size for l in self.lanes)
+    def parked(self, lane, without=()):
+        """A lane none of whose jobs is resident (all evicted) reserves no
+        memory: nothing can run in it, and ephemeral memory only exists during
+        an iteration (Section 3.2.1).  It keeps its id, its jobs and its
+        nominal size L_j and takes its bytes back when one of its jobs is
+        restored.  Without this, a job admitted by priority (Section 4.2: it
+        only has to fit alone) could be blocked for ever by the lanes of the
+        jobs evicted for it.  ``without``: jobs to be treated as evicted."""
+        return not any(j.state == RESIDENT and j.lane == lane.id and j not in without
+                       for j in self.jobs)
+
+    def eff(self, lane, without=()):
+        return 0 if self.parked(lane, without) else lane.size
+
+    def sum_L(self, without=()):
+        return sum(self.eff(l, without) for l in self.lanes)
 
     def floor(self):
         """Lowest address of the ephemeral region = end of the persistent region."""
@@ -106,7 +120,7 @@ class Pool:
         (Section 3.3.1)."""
         top = self.C
         for l in self.lanes:
-            top -= l.size
+            top -= self.eff(l)
             if l.id == lane_id:
                 return top
         raise KeyError(lane_id)
@@ -183,30 +197,33 @@ class Pool:
         job.off = off
 
     # ------------------------------------------------------- Algorithm 1
-    def find_lane(self, P, E, sum_P=None):
+    def find_lane(self, P, E, without=()):
         """FindLane of Algorithm 1.  Returns ('new', None) / ('use', lane) /
-        ('grow', lane) or None.  ``sum_P`` overrides the persistent total of
-        the resident jobs (used to ask "would it fit if these were evicted").
+        ('grow', lane) or None.  ``without`` lists resident jobs to be treated
+        as evicted (used to ask "would it fit if these were evicted").
 
         Readings: the existing-lane branch also needs sum P_i + P + sum L_j <= C
         (the text after the algorithm says a lane is returned only once the
         safety condition is met); "best match" = least slack L_j - E, then
         fewest jobs in the lane, then oldest lane; the replace branch only
         looks at lanes smaller than E (it must never shrink a lane below the
-        peak of a job already in it); the number of lanes may be capped."""
-        S = (self.sum_P() if sum_P is None else sum_P) + P
-        SL = self.sum_L()
+        peak of a job already in it); the number of lanes may be capped; a
+        parked lane (no resident job) is invisible here: it holds no memory,
+        is not counted, shared or grown."""
+        S = sum(j.P for j in self.resident() if j not in without) + P
+        lanes = [l for l in self.lanes if not self.parked(l, without)]
+        SL = sum(l.size for l in lanes)
         C = self.C
         # open a new lane
-        if (self.max_lanes == 0 or len(self.lanes) < self.max_lanes) and S + SL + E <= C:
+        if (self.max_lanes == 0 or len(lanes) < self.max_lanes) and S + SL + E <= C:
             return ('new', None)
         # use an existing lane
         if S + SL <= C:
-            fits = [l for l in self.lanes if l.size >= E]
+            fits = [l for l in lanes if l.size >= E]
             if fits:
                 return ('use', min(fits, key=lambda l: (l.size - E, l.ref, l.id)))
         # replace (grow) an existing lane, smallest first
-        for l in sorted((l for l in self.lanes if l.size < E), key=lambda l: (l.size, l.id)):
+        for l in sorted((l for l in lanes if l.size < E), key=lambda l: (l.size, l.id)):
             if S + SL - l.size + E <= C:
                 return ('grow', l)
         return None
@@ -236,7 +253,7 @@ class Pool:
         lane.ref += 1
         job.lane = lane.id
         job.attained = self.lane_service_level(lane.id, job)
-        self.place_persistent(job, self.floor())
+        self.place_persistent(job, new_floor)
         job.state = RESIDENT
         job.admit_round = self.round
         self.stats['admitted'] += 1
@@ -269,18 +286,19 @@ class Pool:
         moves persistent memory and does not say what happens to the jobs that
         no longer fit; here their persistent state is evicted to host memory,
         lowest priority first, then largest P, then youngest, and only as many
-        as needed; nothing is evicted when even evicting all would not help."""
+        as needed; nothing is evicted when even evicting all would not help.
+        A lane whose jobs are all evicted is parked (see ``parked``), so a
+        request whose P + E fits the pool is always admitted when every other
+        job has a lower priority."""
         for jid in list(self.Q):
             job = self.jobs[jid]
             action = self.find_lane(job.P, job.E)
             if action is None and self.policy == PRIORITY:
                 victims = sorted((v for v in self.resident() if v.priority < job.priority and not v.held),
                                  key=lambda v: (v.priority, -v.P, -v.id))
-                S = self.sum_P()
                 need = None
                 for n in range(1, len(victims) + 1):
-                    S -= victims[n - 1].P
-                    if self.find_lane(job.P, job.E, sum_P=S) is not None:
+                    if self.find_lane(job.P, job.E, without=victims[:n]) is not None:
                         need = n
                         break
                 if need is not None:
@@ -318,11 +336,12 @@ class Pool:
             self.Q.remove(jid)
             job.state = DONE
             return OK
-        job.state, job.host = DONE, None
         lane = self.lane_by_id(job.lane)
+        was_parked = self.parked(lane)
+        job.state, job.host = DONE, None
         lane.ref -= 1
         if lane.ref == 0:
-            behind = sum(1 for l in self.lanes if l.id > lane.id)
+            behind = sum(1 for l in self.lanes if l.id > lane.id) if not was_parked else 0
             self.lanes.remove(lane)
             self.stats['lanes_deleted'] += 1
             self.events.append((EV_LANE_DEL, lane.id, 0))
@@ -341,17 +360,38 @@ class Pool:
             if need < lane.size:
                 lane.size = need
                 behind = sum(1 for l in self.lanes if l.id > lane.id)
-                self.stats['lanes_moved'] += behind
+                if not was_parked:
+                    self.stats['lanes_moved'] += behind
                 self.events.append((EV_LANE_SHRINK, lane.id, need))
+        if lane.ref > 0 and not was_parked:
+            self.note_parked(lane)
         self.process_requests()
         # bring back jobs that priority admission pushed out, oldest first
         for v in self.jobs:
-            if v.state == EVICTED and v.auto_evicted and \
-                    self.sum_P() + v.P + self.sum_L() <= self.C:
+            if v.state == EVICTED and v.auto_evicted and self.can_restore(v):
                 self.switch_in(v.id)
         return OK
 
     # ------------------------------------------------------------- switching
+    def note_parked(self, lane):
+        """Called after a job of ``lane`` stopped being resident: if it was the
+        last one, the lane is parked from now on and younger lanes slide up."""
+        if self.parked(lane):
+            self.stats['lanes_moved'] += sum(1 for l in self.lanes if l.id > lane.id)
+            self.events.append((EV_LANE_PARK, lane.id, lane.size))
+
+    def can_restore(self, job):
+        """Safety condition for bringing an evicted job back; a parked lane
+        needs its bytes again, and counts against the lane cap again."""
+        lane = self.lane_by_id(job.lane)
+        back = 0
+        if self.parked(lane):
+            active = sum(1 for l in self.lanes if not self.parked(l))
+            if self.max_lanes and active >= self.max_lanes:
+                return False
+            back = lane.size
+        return self.sum_P() + job.P + self.sum_L() + back <= self.C
+
     def evict(self, job, auto):
         if self.mem is not None:
             job.host = self.mem[job.off:job.off + job.P].copy()
@@ -359,6 +399,7 @@ class Pool:
         self.stats['evictions'] += 1
         self.stats['bytes_d2h'] += job.P
         self.events.append((EV_EVICT, job.id, job.P))
+        self.note_parked(self.lane_by_id(job.lane))
 
     def switch_out(self, jid):
         if not (0 <= jid < len(self.jobs)):
@@ -400,10 +441,16 @@ class Pool:
         job = self.jobs[jid]
         if job.state != EVICTED:
             return EINVAL
-        if self.sum_P() + job.P + self.sum_L() > self.C:
+        if not self.can_restore(job):
             return ENOMEM
-        self.place_persistent(job, self.floor())
+        lane = self.lane_by_id(job.lane)
+        unpark = self.parked(lane)
+        # a parked lane takes its bytes back: the block goes below the lowered floor
+        self.place_persistent(job, self.floor() - (lane.size if unpark else 0))
         job.state, job.auto_evicted = RESIDENT, False
+        if unpark:
+            self.stats['lanes_moved'] += sum(1 for l in self.lanes if l.id > lane.id)
+            self.events.append((EV_LANE_UNPARK, lane.id, lane.size))
         if self.mem is not None:
             self.mem[job.off:job.off + job.P] = job.host
         job.host = None
@@ -487,9 +534,11 @@ class Pool:
         top = C
         for l in self.lanes:
             base = self.lane_base(l.id)
-            assert base + l.size == top
+            assert base + self.eff(l) == top
             top = base
         assert top == self.floor()
+        if self.max_lanes:
+            assert sum(1 for l in self.lanes if not self.parked(l)) <= self.max_lanes
         assert all(j.state == RESIDENT for j in self.jobs if j.held)
         # persistent blocks: disjoint, granule aligned, below the floor
         cur = 0

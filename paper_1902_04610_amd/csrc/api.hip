@@ -27,7 +27,7 @@ struct HipOps : DeviceOps {
     std::string *error = nullptr;
     uint64_t copy_launches = 0;
     // transfers begun and not yet ended (job id -> fence on the pool's stream, completion event)
-    struct Transfer { hipEvent_t fence, done; };
+    struct Transfer { hipEvent_t fence, done; bool failed; };
     std::map<int32_t, Transfer> inflight;
 
     bool present() const override { return base != nullptr; }
@@ -184,6 +184,14 @@ int32_t salus_lane_alloc(salus_pool_t *pool, uint64_t P, uint64_t E, int32_t pri
 int32_t salus_lane_free(salus_pool_t *pool, int32_t job)
 {
     CHECK_POOL(pool);
+    // a job whose transfer failed can only be given up: its hold is dropped here
+    auto it = pool->ops.inflight.find(job);
+    if (it != pool->ops.inflight.end() && it->second.failed) {
+        (void)hipEventDestroy(it->second.fence);
+        (void)hipEventDestroy(it->second.done);
+        pool->ops.inflight.erase(it);
+        pool->core->drop_hold(job);
+    }
     return done(pool, pool->core->finish(job));
 }
 
@@ -637,7 +645,8 @@ static int32_t start_transfer(salus_pool *pool, int32_t job, void *host, uint64_
         e = to_host ? hipMemcpyAsync(host, ops.base + off, len, hipMemcpyDeviceToHost, copy_stream)
                     : hipMemcpyAsync(ops.base + off, host, len, hipMemcpyHostToDevice, copy_stream);
     if (e == hipSuccess) e = hipEventRecord(t.done, copy_stream);
-    ops.inflight[job] = t;      // also on failure: salus_switch_*_end releases the events
+    t.failed = e != hipSuccess;
+    ops.inflight[job] = t;      // also on failure: the events are released when the job is freed
     if (e != hipSuccess) return set_error(pool, SALUS_EHIP, std::string("transfer: ") + hipGetErrorString(e));
     return SALUS_OK;
 }
@@ -649,12 +658,20 @@ static int32_t finish_transfer(salus_pool *pool, int32_t job, int32_t wait)
     HipOps &ops = pool->ops;
     auto it = ops.inflight.find(job);
     if (it == ops.inflight.end()) return SALUS_OK;
+    if (it->second.failed)
+        return set_error(pool, SALUS_EHIP, "the job's transfer failed; its bytes are not where they "
+                                           "should be: free the job with salus_lane_free");
     hipError_t e = wait ? hipEventSynchronize(it->second.done) : hipEventQuery(it->second.done);
     if (e == hipErrorNotReady) return set_error(pool, SALUS_EBUSY, "transfer still in flight");
+    if (e != hipSuccess) {
+        // the job stays held and the failure is remembered: a second call must not
+        // find "nothing in flight" and complete the bookkeeping of a copy that never landed
+        it->second.failed = true;
+        return set_error(pool, SALUS_EHIP, std::string("transfer: ") + hipGetErrorString(e));
+    }
     (void)hipEventDestroy(it->second.fence);
     (void)hipEventDestroy(it->second.done);
     ops.inflight.erase(it);
-    if (e != hipSuccess) return set_error(pool, SALUS_EHIP, std::string("transfer: ") + hipGetErrorString(e));
     return SALUS_OK;
 }
 
@@ -740,11 +757,11 @@ int32_t salus_lanes(salus_pool_t *pool, int32_t *ids, uint64_t *offs, uint64_t *
     uint64_t top = pool->core->capacity();
     uint32_t k = 0;
     for (const Lane &l : lanes) {
-        top -= l.size;
+        top -= l.bytes();
         if (k < cap) {
             if (ids) ids[k] = l.id;
             if (offs) offs[k] = top;
-            if (sizes) sizes[k] = l.size;
+            if (sizes) sizes[k] = l.bytes();
             ++k;
         }
     }

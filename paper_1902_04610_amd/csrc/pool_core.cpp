@@ -26,9 +26,9 @@ uint64_t PoolCore::lane_base(int32_t lane_id, uint64_t *size) const
 {
     uint64_t top = C_;
     for (const Lane &l : lanes_) {
-        top -= l.size;
+        top -= l.bytes();
         if (l.id == lane_id) {
-            if (size) *size = l.size;
+            if (size) *size = l.bytes();
             return top;
         }
     }
@@ -36,24 +36,38 @@ uint64_t PoolCore::lane_base(int32_t lane_id, uint64_t *size) const
     return UINT64_MAX;
 }
 
+size_t PoolCore::lane_index(int32_t lane_id) const
+{
+    for (size_t i = 0; i < lanes_.size(); ++i)
+        if (lanes_[i].id == lane_id) return i;
+    return lanes_.size();
+}
+
 // FindLane of Algorithm 1 under the safety condition of Section 3.3.2.
-// residentP = persistent bytes of the jobs that would stay resident.
-PoolCore::Choice PoolCore::find_lane(uint64_t P, uint64_t E, uint64_t residentP) const
+// residentP = persistent bytes of the jobs that would stay resident.  Parked
+// lanes are invisible: they hold no bytes and are not counted, shared or grown.
+PoolCore::Choice PoolCore::find_lane(uint64_t P, uint64_t E, uint64_t residentP,
+                                     const std::vector<uint32_t> *gone) const
 {
     const uint64_t S = residentP + P;
+    auto active = [&](size_t i) { return lanes_[i].resident > (gone ? (*gone)[i] : 0u); };
+    uint64_t SL = 0;
+    size_t count = 0;
+    for (size_t i = 0; i < lanes_.size(); ++i)
+        if (active(i)) { SL += lanes_[i].size; ++count; }
     Choice c;
     // 1. open a new lane
-    if ((max_lanes_ == 0 || lanes_.size() < max_lanes_) && S + sumL_ + E <= C_) {
+    if ((max_lanes_ == 0 || count < max_lanes_) && S + SL + E <= C_) {
         c.kind = NEW;
         return c;
     }
     // 2. share an existing lane that is large enough: least slack, then fewest
     //    jobs, then oldest
-    if (S + sumL_ <= C_) {
+    if (S + SL <= C_) {
         bool found = false;
         for (size_t i = 0; i < lanes_.size(); ++i) {
             const Lane &l = lanes_[i];
-            if (l.size < E) continue;
+            if (!active(i) || l.size < E) continue;
             if (!found) { found = true; c.index = i; continue; }
             const Lane &b = lanes_[c.index];
             if (l.size - E < b.size - E || (l.size == b.size && l.ref < b.ref)) c.index = i;
@@ -63,11 +77,11 @@ PoolCore::Choice PoolCore::find_lane(uint64_t P, uint64_t E, uint64_t residentP)
     // 3. grow a lane that is too small, smallest first (oldest among equals)
     std::vector<size_t> small;
     for (size_t i = 0; i < lanes_.size(); ++i)
-        if (lanes_[i].size < E) small.push_back(i);
+        if (active(i) && lanes_[i].size < E) small.push_back(i);
     std::stable_sort(small.begin(), small.end(),
                      [&](size_t a, size_t b) { return lanes_[a].size < lanes_[b].size; });
     for (size_t i : small)
-        if (S + sumL_ - lanes_[i].size + E <= C_) {
+        if (S + SL - lanes_[i].size + E <= C_) {
             c.kind = GROW;
             c.index = i;
             return c;
@@ -104,8 +118,11 @@ int PoolCore::do_compact(std::vector<salus_move> *plan_out)
     int rc = 0;
     if (!plan.empty() && dev_->present()) {
         const auto &top = *blocks_.rbegin();
-        const uint64_t high = round_up(top.first + jobs_[top.second].P, 256);
-        rc = dev_->slide(plan.data(), (uint32_t)plan.size(), high, high < C_ ? C_ - high : 0);
+        // staging may only use the gap between the highest live block and the
+        // ephemeral region: lanes hold inputs and outputs that callers keep
+        // across rounds, and other lanes may be iterating during a switch_in
+        const uint64_t high = round_up(top.first + jobs_[top.second].P, 256), fl = floor();
+        rc = dev_->slide(plan.data(), (uint32_t)plan.size(), high, high < fl ? fl - high : 0);
     }
     if (rc) { error = "device compaction failed"; return SALUS_EHIP; }
     for (const auto &kv : packed) jobs_[kv.second].off = kv.first;
@@ -144,12 +161,14 @@ int PoolCore::admit(Job &j, Choice c)
     uint64_t high = blocks_.empty() ? 0 : blocks_.rbegin()->first + jobs_[blocks_.rbegin()->second].P;
     if (high > new_floor)
         if (int rc = do_compact(nullptr)) return rc;
+    const uint64_t old_size = c.kind == GROW ? lanes_[c.index].size : 0;
+    const uint64_t old_moved = stats.lanes_moved;
+    const size_t mark = events.size();
     if (c.kind == NEW) {
-        lanes_.push_back({next_lane_++, j.E, 0});
+        lanes_.push_back({next_lane_, j.E, 0, 0});
         c.index = lanes_.size() - 1;
         sumL_ += j.E;
-        stats.lanes_opened += 1;
-        log(SALUS_EV_LANE_NEW, lanes_.back().id, j.E);
+        log(SALUS_EV_LANE_NEW, next_lane_, j.E);
     } else if (c.kind == GROW) {
         Lane &l = lanes_[c.index];
         sumL_ += j.E - l.size;
@@ -157,11 +176,29 @@ int PoolCore::admit(Job &j, Choice c)
         stats.lanes_moved += lanes_.size() - 1 - c.index;
         log(SALUS_EV_LANE_GROW, l.id, l.size);
     }
+    if (int rc = place(j, floor())) {
+        // the device failed while making room: the lane change is undone and
+        // the request stays where it was
+        if (c.kind == NEW) {
+            sumL_ -= j.E;
+            lanes_.pop_back();
+        } else if (c.kind == GROW) {
+            sumL_ -= j.E - old_size;
+            lanes_[c.index].size = old_size;
+            stats.lanes_moved = old_moved;
+        }
+        if (c.kind != USE) events.erase(events.begin() + mark);
+        return rc;
+    }
     Lane &l = lanes_[c.index];
+    if (c.kind == NEW) {
+        next_lane_ += 1;
+        stats.lanes_opened += 1;
+    }
     l.ref += 1;
+    l.resident += 1;
     j.lane = l.id;
     j.attained = entry_level(j);
-    if (int rc = place(j, floor())) return rc;
     j.state = SALUS_JOB_RESIDENT;
     sumP_ += j.P;
     j.admit_round = round_;
@@ -213,7 +250,36 @@ int PoolCore::evict(Job &j, bool automatic, void *pinned, bool copied)
     stats.evictions += 1;
     stats.bytes_d2h += j.P;
     log(SALUS_EV_EVICT, j.id, j.P);
+    left_device(j);
     return SALUS_OK;
+}
+
+// One resident job fewer in j's lane; with none left the lane is parked and the
+// younger lanes slide up (bookkeeping only).
+void PoolCore::left_device(Job &j)
+{
+    const size_t i = lane_index(j.lane);
+    Lane &l = lanes_[i];
+    if (--l.resident == 0 && l.ref > 0) {
+        sumL_ -= l.size;
+        stats.lanes_moved += lanes_.size() - 1 - i;
+        log(SALUS_EV_LANE_PARK, l.id, l.size);
+    }
+}
+
+// Safety condition for bringing an evicted job back: a parked lane needs its
+// bytes again and counts against the lane cap again.
+bool PoolCore::can_restore(const Job &j) const
+{
+    const Lane &l = lanes_[lane_index(j.lane)];
+    uint64_t back = 0;
+    if (l.parked()) {
+        size_t active = 0;
+        for (const Lane &o : lanes_) active += !o.parked();
+        if (max_lanes_ && active >= max_lanes_) return false;
+        back = l.size;
+    }
+    return sumP_ + j.P + sumL_ + back <= C_;
 }
 
 // ProcessRequests of Algorithm 1, plus priority admission (Section 4.2).
@@ -238,17 +304,19 @@ void PoolCore::process_requests()
             });
             uint64_t left = sumP_;
             size_t need = 0;
+            std::vector<uint32_t> gone(lanes_.size(), 0);
             for (size_t n = 0; n < victims.size(); ++n) {
                 left -= jobs_[victims[n]].P;
-                if (find_lane(j.P, j.E, left).kind != NONE) { need = n + 1; break; }
+                gone[lane_index(jobs_[victims[n]].lane)] += 1;
+                if (find_lane(j.P, j.E, left, &gone).kind != NONE) { need = n + 1; break; }
             }
             for (size_t n = 0; n < need; ++n)
                 if (evict(jobs_[victims[n]], true, nullptr)) return;
             if (need) c = find_lane(j.P, j.E, sumP_);
         }
         if (c.kind != NONE) {
+            if (admit(j, c)) return;        // the request stays queued when the device fails
             queue_.erase(std::find(queue_.begin(), queue_.end(), id));
-            if (admit(j, c)) return;
         }
     }
 }
@@ -289,26 +357,28 @@ int32_t PoolCore::finish(int32_t id)
         j.state = SALUS_JOB_DONE;
         return SALUS_OK;
     }
-    if (j.state == SALUS_JOB_RESIDENT) {
+    const bool was_resident = j.state == SALUS_JOB_RESIDENT;
+    if (was_resident) {
         blocks_.erase(j.off);
         sumP_ -= j.P;
     }
     if (j.host && j.host_owned) dev_->pinned_free(j.host);
     j.host = nullptr;
     j.state = SALUS_JOB_DONE;
-    for (size_t i = 0; i < lanes_.size(); ++i) {
-        if (lanes_[i].id != j.lane) continue;
-        if (--lanes_[i].ref == 0) {
-            uint64_t behind = lanes_.size() - 1 - i;
-            sumL_ -= lanes_[i].size;
-            log(SALUS_EV_LANE_DEL, lanes_[i].id, 0);
-            lanes_.erase(lanes_.begin() + i);
-            stats.lanes_deleted += 1;
-            if (behind) {   // younger lanes slide: bookkeeping only
-                stats.lanes_moved += behind;
-                log(SALUS_EV_LANE_MOVED, behind, 0);
-            }
-        } else if (shrink_lanes_) {
+    const size_t i = lane_index(j.lane);
+    const bool was_parked = lanes_[i].parked();
+    if (--lanes_[i].ref == 0) {
+        const uint64_t behind = was_parked ? 0 : lanes_.size() - 1 - i;
+        sumL_ -= lanes_[i].bytes();
+        log(SALUS_EV_LANE_DEL, lanes_[i].id, 0);
+        lanes_.erase(lanes_.begin() + i);
+        stats.lanes_deleted += 1;
+        if (behind) {   // younger lanes slide: bookkeeping only
+            stats.lanes_moved += behind;
+            log(SALUS_EV_LANE_MOVED, behind, 0);
+        }
+    } else {
+        if (shrink_lanes_) {
             // Section 3.3.2 states L_j = max E_i; fall back to the largest peak
             // still in the lane (younger lanes slide up, nothing is copied)
             uint64_t need = 0;
@@ -317,19 +387,20 @@ int32_t PoolCore::finish(int32_t id)
                     m.lane == lanes_[i].id)
                     need = std::max(need, m.E);
             if (need < lanes_[i].size) {
-                sumL_ -= lanes_[i].size - need;
+                if (!was_parked) {
+                    sumL_ -= lanes_[i].size - need;
+                    stats.lanes_moved += lanes_.size() - 1 - i;
+                }
                 lanes_[i].size = need;
-                stats.lanes_moved += lanes_.size() - 1 - i;
                 log(SALUS_EV_LANE_SHRINK, lanes_[i].id, need);
             }
         }
-        break;
+        if (was_resident) left_device(j);     // may park the lane: only evicted jobs remain
     }
     error.clear();
     process_requests();
     for (size_t v = 0; v < jobs_.size(); ++v)
-        if (jobs_[v].state == SALUS_JOB_EVICTED && jobs_[v].auto_evicted &&
-            sumP_ + jobs_[v].P + sumL_ <= C_)
+        if (jobs_[v].state == SALUS_JOB_EVICTED && jobs_[v].auto_evicted && can_restore(jobs_[v]))
             if (switch_in((int32_t)v)) break;
     return error.empty() ? SALUS_OK : SALUS_EHIP;
 }
@@ -392,6 +463,11 @@ int32_t PoolCore::end_in(int32_t id)
     return SALUS_OK;
 }
 
+void PoolCore::drop_hold(int32_t id)
+{
+    if (id >= 0 && (size_t)id < jobs_.size()) jobs_[id].held = jobs_[id].leaving = false;
+}
+
 int32_t PoolCore::switch_in(int32_t id) { return switch_in_impl(id, true); }
 
 int32_t PoolCore::switch_in_impl(int32_t id, bool copy_now)
@@ -401,8 +477,19 @@ int32_t PoolCore::switch_in_impl(int32_t id, bool copy_now)
         return SALUS_EINVAL;
     }
     Job &j = jobs_[id];
-    if (sumP_ + j.P + sumL_ > C_) { error = "no room to restore the job"; return SALUS_ENOMEM; }
-    if (int rc = place(j, floor())) return rc;
+    if (!can_restore(j)) { error = "no room to restore the job"; return SALUS_ENOMEM; }
+    const size_t li = lane_index(j.lane);
+    Lane &l = lanes_[li];
+    const bool unpark = l.parked();
+    // a parked lane takes its bytes back: the block goes below the lowered floor
+    // (blocks in the way are compacted while the old floor still holds)
+    if (int rc = place(j, floor() - (unpark ? l.size : 0))) return rc;
+    if (unpark) {
+        sumL_ += l.size;
+        stats.lanes_moved += lanes_.size() - 1 - li;
+        log(SALUS_EV_LANE_UNPARK, l.id, l.size);
+    }
+    l.resident += 1;
     j.state = SALUS_JOB_RESIDENT;
     j.auto_evicted = false;
     sumP_ += j.P;
@@ -448,14 +535,18 @@ int32_t PoolCore::query(int32_t id, salus_job_info *o) const
     o->priority = j.priority;
     o->auto_evicted = j.auto_evicted;
     o->in_transit = j.held;
-    o->reserved = 0;
+    o->lane_parked = 0;
     o->P = j.P;
     o->E = j.E;
     o->persist_off = j.state == SALUS_JOB_RESIDENT ? j.off : UINT64_MAX;
     o->lane_off = UINT64_MAX;
     o->lane_size = 0;
-    if (j.state == SALUS_JOB_RESIDENT || j.state == SALUS_JOB_EVICTED)
-        o->lane_off = lane_base(j.lane, &o->lane_size);
+    if (j.state == SALUS_JOB_RESIDENT || j.state == SALUS_JOB_EVICTED) {
+        const Lane &l = lanes_[lane_index(j.lane)];
+        o->lane_off = lane_base(j.lane);
+        o->lane_size = l.size;
+        o->lane_parked = l.parked();
+    }
     o->pending = j.pending;
     o->served = j.served;
     o->cost = j.cost;

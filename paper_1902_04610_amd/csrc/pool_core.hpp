@@ -21,8 +21,8 @@ struct DeviceOps {
     virtual int evict(void *host, uint64_t off, uint64_t n) = 0;      // device -> host
     virtual int restore(uint64_t off, const void *host, uint64_t n) = 0;
     // moves in ascending address order, every dst below its src; [free_off,
-    // free_off + free_len) lies above all live blocks and may be used as staging
-    // (ephemeral memory is dead between iterations, Section 3.2.2)
+    // free_off + free_len) is the unused gap between the highest live block and
+    // the ephemeral region and may be used as staging (possibly empty)
     virtual int slide(const salus_move *moves, uint32_t n, uint64_t free_off, uint64_t free_len) = 0;
     virtual void *pinned_alloc(uint64_t n) = 0;
     virtual void pinned_free(void *p) = 0;
@@ -49,6 +49,11 @@ struct Lane {
     int32_t id;
     uint64_t size;               // L_j
     uint32_t ref;                // jobs assigned to the lane
+    uint32_t resident;           // of those, jobs whose persistent state is on the device
+    // A lane without a resident job is parked: nothing can run in it, so it
+    // reserves no bytes until one of its jobs is restored (it keeps id, jobs and L_j).
+    bool parked() const { return resident == 0; }
+    uint64_t bytes() const { return resident ? size : 0; }
 };
 
 class PoolCore {
@@ -71,6 +76,7 @@ public:
     int32_t end_out(int32_t job);
     int32_t begin_in(int32_t job, void **host, uint64_t *off, uint64_t *len);
     int32_t end_in(int32_t job);
+    void drop_hold(int32_t job);     // a transfer failed: the job may now be freed (and only that)
     int32_t compact(std::vector<salus_move> *plan);
 
     const Job *job(int32_t id) const {
@@ -90,7 +96,12 @@ private:
     enum Kind { NONE, NEW, USE, GROW };
     struct Choice { Kind kind = NONE; size_t index = 0; };
 
-    Choice find_lane(uint64_t P, uint64_t E, uint64_t residentP) const;
+    // `gone`: per lane index, resident jobs to be counted as evicted (may be null)
+    Choice find_lane(uint64_t P, uint64_t E, uint64_t residentP,
+                     const std::vector<uint32_t> *gone = nullptr) const;
+    bool can_restore(const Job &j) const;
+    void left_device(Job &j);        // a resident job of a lane was evicted or finished
+    size_t lane_index(int32_t lane_id) const;
     void process_requests();
     int admit(Job &j, Choice c);
     uint64_t entry_level(const Job &j) const;
@@ -111,7 +122,7 @@ private:
     std::vector<Lane> lanes_;             // creation order == address order from the top
     std::deque<int32_t> queue_;           // Q of Algorithm 1
     std::map<uint64_t, int32_t> blocks_;  // live persistent blocks: offset -> job
-    uint64_t sumP_ = 0, sumL_ = 0;        // over resident jobs / over lanes
+    uint64_t sumP_ = 0, sumL_ = 0;        // over resident jobs / over lanes that are not parked
     int32_t next_lane_ = 0;
     uint64_t round_ = 0;
 };

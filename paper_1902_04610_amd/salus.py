@@ -9,7 +9,8 @@ import os
 import torch  # noqa: F401  (first, so that the HIP runtime already loaded by torch is the one the library binds to)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsalus.so")
+# SALUS_LIBRARY names another build of the same sources (the sanitizer build of the tests)
+LIB_PATH = os.environ.get("SALUS_LIBRARY") or os.path.join(_HERE, "libsalus.so")
 
 OK, QUEUED = 0, 1
 EINVAL, ENOMEM, ENOTRESIDENT, EBUSY, ENEVER, EHIP, ETIMEOUT = -1, -2, -3, -4, -5, -6, -7
@@ -30,7 +31,7 @@ class Config(C.Structure):
 
 class JobInfo(C.Structure):
     _fields_ = [("state", C.c_int32), ("lane", C.c_int32), ("priority", C.c_int32),
-                ("auto_evicted", C.c_int32), ("in_transit", C.c_int32), ("reserved", C.c_int32),
+                ("auto_evicted", C.c_int32), ("in_transit", C.c_int32), ("lane_parked", C.c_int32),
                 ("P", C.c_uint64), ("E", C.c_uint64),
                 ("persist_off", C.c_uint64), ("lane_off", C.c_uint64), ("lane_size", C.c_uint64),
                 ("pending", C.c_uint64), ("served", C.c_uint64),

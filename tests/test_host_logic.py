@@ -39,7 +39,7 @@ def snapshot_oracle(p):
                      p.lane_by_id(j.lane).size if in_lane else 0,
                      j.pending, j.served, int(j.auto_evicted and j.state == op.EVICTED), int(j.held),
                      j.cost, j.attained))
-    lanes = [(l.id, p.lane_base(l.id), l.size) for l in p.lanes]
+    lanes = [(l.id, p.lane_base(l.id), p.eff(l)) for l in p.lanes]
     return jobs, lanes
 
 
@@ -265,6 +265,26 @@ def test_workload4_schedule_matches_oracle_over_500_rounds():
     st = g.stats()
     assert (st["evictions"], st["restores"]) == (9, 9) == (o.stats["evictions"], o.stats["restores"])
     assert st["bytes_d2h"] == st["bytes_h2d"] == 9 * (20 * GB // 256 * 256)
+    assert [tuple(e) for e in o.events] == g.poll_events()
+    g.close()
+
+
+def test_priority_job_that_fits_alone_is_admitted_through_the_library():
+    """Section 4.2 through the C ABI: the lane of the evicted job is parked, so the
+    urgent job (P + E <= C) gets in; the lane and the job come back afterwards."""
+    g = salus.Pool(None, 100 * 256, granule=256, policy=salus.POLICY_PRIORITY)
+    o = op.Pool(100 * 256, granule=256, policy=op.PRIORITY)
+    assert g.lane_alloc(10 * 256, 60 * 256, 0, 50) == o.job_arrive(10 * 256, 60 * 256, 0, 50) == (salus.OK, 0)
+    assert g.lane_alloc(50 * 256, 45 * 256, 9, 5) == o.job_arrive(50 * 256, 45 * 256, 9, 5) == (salus.OK, 1)
+    low, high = g.job_query(0), g.job_query(1)
+    assert low.state == salus.JOB_EVICTED and low.lane_parked == 1 and low.lane_size == 60 * 256
+    assert high.lane_parked == 0 and high.lane_off == 55 * 256 and high.persist_off == 0
+    assert g.lanes() == [(0, 100 * 256, 0), (1, 55 * 256, 45 * 256)]
+    assert g.schedule_iteration() == o.schedule_iteration() == [(1, 1)]
+    assert g.switch_in(0) == o.switch_in(0) == salus.ENOMEM
+    assert g.lane_free(1) == o.job_finish(1) == salus.OK
+    low = g.job_query(0)
+    assert low.state == salus.JOB_RESIDENT and low.lane_parked == 0 and low.lane_off == 40 * 256
     assert [tuple(e) for e in o.events] == g.poll_events()
     g.close()
 

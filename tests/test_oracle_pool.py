@@ -346,10 +346,97 @@ def test_priority_admission_evicts_and_restores():
 
 
 def test_priority_eviction_is_skipped_when_it_cannot_help():
+    """Nothing is evicted for a request that would not fit even then: the room is
+    held by a job of the same priority, which is never a victim."""
     p = op.Pool(100, granule=1, policy=op.PRIORITY)
-    _, a = p.job_arrive(10, 60, priority=0, pending=5)
-    st, b = p.job_arrive(50, 45, priority=9, pending=5)   # even alone beside lane 0 (60): 50+60 > 100
-    assert st == op.IS_QUEUED and p.jobs[a].state == op.RESIDENT and p.stats['evictions'] == 0
+    _, a = p.job_arrive(30, 40, priority=9, pending=5)
+    _, low = p.job_arrive(10, 10, priority=0, pending=5)
+    st, b = p.job_arrive(35, 40, priority=9, pending=5)   # without low: 30+35 + lane 40 = 105 > 100
+    assert st == op.IS_QUEUED and p.stats['evictions'] == 0
+    assert p.jobs[low].state == op.RESIDENT and p.jobs[a].state == op.RESIDENT
+    p.check_invariants()
+
+
+def test_priority_job_that_fits_alone_is_admitted_whatever_runs():
+    """Section 4.2: the higher-priority job is admitted as long as it could run
+    alone (P + E <= C), regardless of the jobs already running.  The lane of
+    the job evicted for it must not stand in the way: a lane with no resident
+    job is parked (reserves nothing) until one of its jobs returns."""
+    mem = np.zeros(100, np.uint8)
+    p = op.Pool(100, granule=1, policy=op.PRIORITY, mem=mem)
+    _, low = p.job_arrive(10, 60, priority=0, pending=50)
+    mem[0:10] = np.arange(1, 11)
+    assert p.lane_base(0) == 40
+    st, high = p.job_arrive(50, 45, priority=9, pending=5)     # 50 + 45 = 95 <= 100
+    assert st == op.OK and p.jobs[low].state == op.EVICTED and p.jobs[low].auto_evicted
+    assert [l.id for l in p.lanes] == [0, 1] and p.parked(p.lanes[0]) and not p.parked(p.lanes[1])
+    assert p.sum_L() == 45 and p.floor() == 55 and p.lane_base(1) == 55 and p.jobs[high].off == 0
+    kinds = [e[0] for e in p.events]
+    assert kinds[-4:] == [op.EV_EVICT, op.EV_LANE_PARK, op.EV_LANE_NEW, op.EV_ADMIT]
+    p.check_invariants()
+    mem[:] = 0x77
+    assert p.schedule_iteration() == [(high, 1)]
+    assert p.switch_in(low) == op.ENOMEM                       # 50 + 10 + 45 + 60 > 100
+    p.job_finish(high)
+    assert p.jobs[low].state == op.RESIDENT and p.jobs[low].off == 0
+    assert (mem[0:10] == np.arange(1, 11)).all()
+    assert not p.parked(p.lanes[0]) and p.lane_base(0) == 40 and p.sum_L() == 60
+    assert p.events[-2] == (op.EV_LANE_UNPARK, 0, 60) and p.events[-1] == (op.EV_RESTORE, low, 0)
+    p.check_invariants()
+
+
+def test_parked_lane_rules():
+    # a lane is parked only when ALL its jobs are evicted, and any restore unparks it
+    p = op.Pool(100, granule=1, max_lanes=2, policy=op.RR)
+    a = p.job_arrive(10, 30)[1]
+    b = p.job_arrive(10, 20)[1]                 # lane 1
+    c = p.job_arrive(10, 30)[1]                 # shares lane 0 (exact fit)
+    assert [p.jobs[x].lane for x in (a, b, c)] == [0, 1, 0]
+    assert p.switch_out(a) == op.OK and p.sum_L() == 50 and p.lane_base(1) == 50
+    assert p.switch_out(c) == op.OK and p.sum_L() == 20 and p.lane_base(1) == 80   # lane 1 slid up
+    p.check_invariants()
+    # parked lanes are invisible to FindLane: not shared, not grown, not counted
+    d = p.job_arrive(10, 30)[1]
+    assert p.jobs[d].lane == 2 and p.lane_base(2) == 50
+    # the cap counts lanes that hold memory: lane 0 cannot come back while two others do
+    assert p.switch_in(a) == op.ENOMEM
+    p.job_finish(b)
+    assert p.switch_in(a) == op.OK and p.lane_base(0) == 70 and p.lane_base(2) == 40
+    assert p.jobs[c].state == op.EVICTED        # its lane is back, the job itself is not
+    p.check_invariants()
+    # a parked lane whose last job finishes is deleted without any slide
+    q = op.Pool(100, granule=1, policy=op.RR)
+    x = q.job_arrive(10, 30)[1]
+    y = q.job_arrive(10, 20)[1]
+    q.switch_out(x)
+    moved = q.stats['lanes_moved']
+    q.job_finish(x)
+    assert [l.id for l in q.lanes] == [1] and q.stats['lanes_moved'] == moved and q.lane_base(1) == 80
+    q.check_invariants()
+
+
+def test_strictly_most_urgent_arrival_is_always_admitted_at_once():
+    """Property behind Section 4.2, on random pools: under PRIORITY an arrival
+    whose priority is above every other job's and whose P + E <= C is resident
+    when job_arrive returns, whatever was running."""
+    rng = np.random.default_rng(11)
+    for trial in range(200):
+        C = int(rng.integers(40, 200))
+        p = op.Pool(C, granule=1, policy=op.PRIORITY, max_lanes=int(rng.integers(0, 4)))
+        for _ in range(int(rng.integers(1, 8))):
+            p.job_arrive(int(rng.integers(1, C // 2)), int(rng.integers(1, C // 2)),
+                         priority=int(rng.integers(0, 5)), pending=3)
+            p.check_invariants()
+        live = [j for j in p.jobs if j.state == op.RESIDENT]
+        for j in live[:int(rng.integers(0, 3))]:
+            p.job_finish(j.id)
+        P = int(rng.integers(1, C))
+        E = int(rng.integers(1, C - P + 1))
+        st, u = p.job_arrive(P, E, priority=9, pending=3)
+        assert st == op.OK, (trial, C, P, E)
+        p.check_invariants()
+        p.job_finish(u)
+        p.check_invariants()
 
 
 # ------------------------------------------------------------------ scheduling
