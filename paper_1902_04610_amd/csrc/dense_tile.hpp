@@ -296,7 +296,7 @@ __device__ inline void dense_f32_tile(const Problem &p, const Tile tile, float *
         if (row >= M || !col_ok) continue;
         f32x4 o;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[i] = activate(own[t * 4 + i], act);
+        for (int i = 0; i < 4; ++i) o[i] = activate_f32(own[t * 4 + i], act);
         *(f32x4 *)((float *)p.Y + (size_t)row * N + ncol) = o;
     }
 }

@@ -17,9 +17,13 @@ struct GroupArgs {
 constexpr int kGemmThreads = 256;
 constexpr int kWaves = 4;
 
-// erf by the rational approximation 7.1.26 of Abramowitz & Stegun (absolute
-// error below 1.5e-7, far inside half a bf16 step): one reciprocal, one
-// exponential and a degree-5 polynomial, no branches.
+// bf16 kernels: erf by the rational approximation 7.1.26 of Abramowitz & Stegun
+// (absolute error below 1.5e-7, far inside half a bf16 step): one reciprocal, one
+// exponential and a degree-5 polynomial, no branches.  The error of the result is
+// 0.5 |z| times that, i.e. it shrinks with the input; it is an *absolute* error in
+// 1 + erf, so for z < -3.5, where 1 + erf itself falls below 5e-4, the relative
+// error of a single output grows - such outputs are below 1e-3 in magnitude and
+// only decide a comparison when a whole matrix consists of them.
 __device__ inline float gelu_fast(float z)
 {
     const float x = fabsf(z) * 0.70710678118654752440f;
@@ -36,6 +40,16 @@ __device__ inline float activate(float z, uint32_t act)
 {
     if (act == 1) return fmaxf(z, 0.0f);
     if (act == 2) return gelu_fast(z);
+    return z;
+}
+
+// float kernels: the bound is relative (1e-5 of the largest output), so GELU is
+// 0.5 z erfc(-z / sqrt 2) with the library's erfc, accurate to a few ulp in the
+// negative tail as well.  These kernels are latency-bound; the cost does not show.
+__device__ inline float activate_f32(float z, uint32_t act)
+{
+    if (act == 1) return fmaxf(z, 0.0f);
+    if (act == 2) return 0.5f * z * erfcf(-0.70710678118654752440f * z);
     return z;
 }
 
