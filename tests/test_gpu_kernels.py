@@ -98,9 +98,10 @@ def run_jobs(jobs, dtype, fuse=False):
         assert st == salus.OK
         q = dp.pool.job_query(jid)
         dims, M = j["dims"], j["M"]
-        Ws = [(rng.standard_normal((K, N)) / np.sqrt(K)).astype(np.float32)
-              for K, N in zip(dims[:-1], dims[1:])]
-        X = rng.uniform(-1, 1, (M, dims[0])).astype(np.float32)
+        # optional: w_scale / w_mean shape the pre-activations (mean w_mean * E[x] per output)
+        Ws = [(j.get("w_scale", 1.0) * rng.standard_normal((K, N)) / np.sqrt(K) + j.get("w_mean", 0.0) / K)
+              .astype(np.float32) for K, N in zip(dims[:-1], dims[1:])]
+        X = rng.uniform(j.get("x_lo", -1), j.get("x_hi", 1), (M, dims[0])).astype(np.float32)
         if dtype == salus.BF16:
             Ws = [synth.f32_to_bf16_bits(w) for w in Ws]
             X = synth.f32_to_bf16_bits(X)
@@ -243,6 +244,32 @@ def test_f32_ragged_shapes(M):
     for o, r, j in zip(outs, refs, jobs):
         assert np.isfinite(o).all(), j
         assert norm_rel_err(o, r) < TOL_F32, (j, norm_rel_err(o, r))
+
+
+def test_f32_gelu_outputs_of_small_magnitude_and_in_the_negative_tail():
+    """The float bound is relative to the largest output of a matrix, so GELU must
+    be accurate relative to its own value: inputs of order 1e-3 (outputs ~ z / 2)
+    and pre-activations that are all in [-6, -3.5], where 1 + erf is 1e-4 .. 1e-9
+    and every output is below 1e-3 in magnitude."""
+    jobs = [dict(M=19, dims=(256, 132), acts=[GELU], x_lo=-1e-3, x_hi=1e-3),
+            dict(M=8, dims=(256, 256, 68), acts=[GELU, GELU], x_lo=-1e-3, x_hi=1e-3),
+            dict(M=33, dims=(128, 260), acts=[GELU], x_lo=0.9, x_hi=1.0, w_scale=0.5, w_mean=-5.0),
+            dict(M=16, dims=(64, 64), acts=[GELU], x_lo=0.99, x_hi=1.0, w_scale=0.05, w_mean=-4.0)]
+    outs, refs, launches = run_jobs(jobs, salus.F32)
+    for o, r, j in zip(outs, refs, jobs):
+        assert np.isfinite(o).all(), j
+        assert np.abs(r).max() < 2e-3, (j, np.abs(r).max())           # the case really is a small-output one
+        assert norm_rel_err(o, r) < TOL_F32, (j, norm_rel_err(o, r))
+    assert (refs[2] <= 0).all() and (refs[3] <= 0).all()              # all in the negative tail
+
+
+def test_bf16_gelu_inputs_of_small_magnitude():
+    """The bf16 kernels' erf approximation has an absolute error, scaled by the
+    input: outputs of order 1e-3 still meet the tight relative bound."""
+    jobs = [dict(M=m, dims=(256, 264), acts=[GELU], x_lo=-1e-3, x_hi=1e-3) for m in (7, 32, 64, 200)]
+    outs, refs, launches = run_jobs(jobs, salus.BF16)
+    for o, r, j in zip(outs, refs, jobs):
+        assert np.abs(r).max() < 2e-3 and norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
 
 
 def test_special_weights_bf16():
