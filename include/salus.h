@@ -248,6 +248,24 @@ int32_t salus_schedule_iteration(salus_pool_t *pool, salus_slot *out, uint32_t c
 int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
                               void *stream);
 
+/* For callers that must not allocate device memory and have no lane room to
+ * spare for scratch (code recorded into a HIP graph, tight serving loops,
+ * harnesses that forbid allocation): salus_grouped_forward with the hidden
+ * activations kept in a fixed array inside the library instead of at h_off in
+ * each job's lane.  h_off is ignored; x and y are still the caller's, inside the
+ * lane.  Same kernels, same launches per layer depth (never depth-fused), same
+ * bits in y.  The round's hidden activations - the sum over its jobs of
+ * salus_forward_work_bytes(), each rounded up to 256 - must fit
+ * SALUS_STATIC_SCRATCH_BYTES, else SALUS_ENOMEM and nothing is launched.  The
+ * call allocates and frees nothing on the device.  One array per GPU, shared
+ * by every pool and every call on that GPU and never cleared (every element
+ * that is read was written earlier in the same call): calls that can overlap on
+ * one GPU - different streams, or different host threads - race on it and must
+ * be ordered by the caller.  The GPU of the pool must be the current device. */
+#define SALUS_STATIC_SCRATCH_BYTES (32ull << 20)
+int32_t salus_grouped_forward_static(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
+                                     void *stream);
+
 /* MANDATORY after fused launches, before their outputs are used: the device-side
  * wait relies on workgroups being dispatched in index order, which the hardware
  * does today but no specification promises; when that fails the launch still

@@ -111,6 +111,34 @@ struct salus_pool {
 #define CHECK_POOL(p) \
     if (!(p)) return SALUS_EINVAL
 
+// Hidden activations of salus_grouped_forward_static.  Every GPU the library runs
+// on holds its own copy of this array until the process ends.  In host code the
+// name below is only a handle for hipGetSymbolAddress, never a device address:
+// host code uses the per-device pointer obtained in static_scratch().
+constexpr uint64_t kStaticScratchBytes = SALUS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static char *g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (looked up once per device).
+static hipError_t static_scratch(char **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = (char *)ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
 static int32_t set_error(salus_pool *p, int32_t code, const std::string &msg)
 {
     p->error = msg;
@@ -291,15 +319,18 @@ uint64_t salus_forward_work_bytes(uint32_t M, const salus_layer *layers, uint32_
     return xp + (n_layers > 1 ? 2 * hs : 0);
 }
 
-int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
-                              void *stream)
+// hidden == nullptr: the hidden activations live at h_off inside each job's lane.
+// Otherwise they are carved out of [hidden, hidden + hidden_bytes), h_off is
+// ignored and the depth-fused path is not taken.
+static int32_t forward_impl(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
+                            void *stream, char *hidden, uint64_t hidden_bytes)
 {
-    CHECK_POOL(pool);
     if (n == 0) return SALUS_OK;
     if (!descs) return set_error(pool, SALUS_EINVAL, "null descriptor array");
     if (!pool->ops.present()) return set_error(pool, SALUS_EINVAL, "pool has no device memory");
     char *base = pool->ops.base;
     uint32_t depth = 0;
+    uint64_t hidden_used = 0;
     std::vector<int32_t> lanes_used;
     struct Resolved { char *w, *x, *y, *xp, *h; uint64_t hstride; };
     std::vector<Resolved> res(n);
@@ -340,14 +371,23 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
         forward_scratch(d.M, d.layers, d.n_layers, d.dtype, &xp_bytes, &hstride);
         const uint64_t hbytes = xp_bytes + (d.n_layers > 1 ? 2 * hstride : 0);
         auto inside = [&](uint64_t off, uint64_t nb) { return off % 16 == 0 && off <= lane_size && nb <= lane_size - off; };
-        if (!inside(d.x_off, xbytes) || !inside(d.y_off, ybytes) || !inside(d.h_off, hbytes))
+        if (!inside(d.x_off, xbytes) || !inside(d.y_off, ybytes) || (!hidden && !inside(d.h_off, hbytes)))
             return set_error(pool, SALUS_EINVAL, "buffer outside the job's lane");
-        if (overlap(d.x_off, xbytes, d.y_off, ybytes) || overlap(d.x_off, xbytes, d.h_off, hbytes) ||
-            overlap(d.y_off, ybytes, d.h_off, hbytes))
+        if (overlap(d.x_off, xbytes, d.y_off, ybytes) ||
+            (!hidden && (overlap(d.x_off, xbytes, d.h_off, hbytes) || overlap(d.y_off, ybytes, d.h_off, hbytes))))
             return set_error(pool, SALUS_EINVAL, "x, y and h ranges overlap");
         char *lane = base + lane_off;
-        res[i] = {base + j->off, lane + d.x_off, lane + d.y_off, lane + d.h_off,
-                  lane + d.h_off + xp_bytes, hstride};
+        char *h = lane + d.h_off;
+        if (hidden) {
+            if (hbytes > hidden_bytes - hidden_used)
+                return set_error(pool, SALUS_ENOMEM,
+                                 "the hidden activations of this round exceed the static scratch of " +
+                                     std::to_string(hidden_bytes) + " bytes");
+            h = hidden + hidden_used;
+            hidden_used += up256(hbytes);
+            if (hidden_used > hidden_bytes) hidden_used = hidden_bytes;
+        }
+        res[i] = {base + j->off, lane + d.x_off, lane + d.y_off, h, h + xp_bytes, hstride};
         depth = std::max(depth, d.n_layers);
     }
     hipStream_t s = (hipStream_t)stream;
@@ -376,7 +416,7 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
     for (int dt = SALUS_F32; dt <= SALUS_BF16; ++dt) {
         // Depth-fused: all layers of all jobs of this type in one launch, if every
         // job is one the weight-streaming kernels take (bf16: at most 32 rows).
-        if (pool->chain) {
+        if (pool->chain && !hidden) {
             bool fits = true, any = false;
             for (uint32_t i = 0; i < n && fits; ++i) {
                 const salus_gemm_desc &d = descs[i];
@@ -422,7 +462,23 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
     return SALUS_OK;
 }
 
+int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
+                              void *stream)
+{
+    CHECK_POOL(pool);
+    return forward_impl(pool, descs, n, stream, nullptr, 0);
+}
 
+int32_t salus_grouped_forward_static(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
+                                     void *stream)
+{
+    CHECK_POOL(pool);
+    char *ptr = nullptr;
+    hipError_t e = static_scratch(&ptr);
+    if (e != hipSuccess)
+        return set_error(pool, SALUS_EHIP, std::string("static scratch: ") + hipGetErrorString(e));
+    return forward_impl(pool, descs, n, stream, ptr, kStaticScratchBytes);
+}
 
 int32_t salus_fused_check(salus_pool_t *pool)
 {

@@ -96,6 +96,7 @@ _PROTOS = {
     "salus_job_read": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
     "salus_schedule_iteration": [C.c_void_p, C.POINTER(Slot), C.c_uint32, C.POINTER(C.c_uint32)],
     "salus_grouped_forward": [C.c_void_p, C.POINTER(GemmDesc), C.c_uint32, C.c_void_p],
+    "salus_grouped_forward_static": [C.c_void_p, C.POINTER(GemmDesc), C.c_uint32, C.c_void_p],
     "salus_train_work_bytes": [C.c_uint32, C.POINTER(TrainLayer), C.c_uint32],
     "salus_forward_work_bytes": [C.c_uint32, C.POINTER(Layer), C.c_uint32, C.c_int32],
     "salus_grouped_train_step": [C.c_void_p, C.POINTER(TrainDesc), C.c_uint32, C.c_void_p],
@@ -261,6 +262,12 @@ class Pool:
             n = len(descs)
         return self._check(self._lib.salus_grouped_forward(self._h, descs, n, stream),
                            (OK, EINVAL, ENOTRESIDENT, EBUSY))
+
+    def grouped_forward_static(self, descs, n=None, stream=None):
+        if n is None:
+            n = len(descs)
+        return self._check(self._lib.salus_grouped_forward_static(self._h, descs, n, stream),
+                           (OK, EINVAL, ENOTRESIDENT, EBUSY, ENOMEM))
 
     @staticmethod
     def make_train_descs(items):
