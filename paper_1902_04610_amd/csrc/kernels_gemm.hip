@@ -14,7 +14,7 @@
 #include <algorithm>
 #include <vector>
 
-#include "dense_tile.hpp"
+#include "dense_tile_n64.hpp"
 
 namespace salus {
 
@@ -23,7 +23,22 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
 {
     __shared__ float lds[reduce_lds_floats<MT * 8>()];
     const Tile tile = find_tile<16 * MT, 128>(a);
-    dense_bf16_tile<MT, TW, NT>(a.p[tile.problem], tile, lds);
+    const Problem &p = a.p[tile.problem];
+    // A job of at most 16 rows takes the one-row-tile path even when the launch holds
+    // larger jobs: its second row tile would only load clamped copies of its last row,
+    // and activation loads count against the compute unit's memory path like weights do.
+    if (MT == 2 && NT && p.M <= 16) dense_bf16_tile<1, TW, NT>(p, tile, lds);
+    else dense_bf16_tile<MT, TW, NT>(p, tile, lds);
+}
+
+// Jobs of 33 .. 128 rows that do not go to the LDS-tiled kernel: row tiles of 64
+// rows, 64 columns wide (see dense_tile_n64.hpp).
+template <bool TW, bool NT>
+__global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16_n64(GroupArgs a)
+{
+    __shared__ float lds[reduce_lds_floats<16>()];
+    const Tile tile = find_tile<64, 64>(a);
+    dense_bf16_tile_n64<4, TW, NT>(a.p[tile.problem], tile, lds);
 }
 
 template <int MT>
@@ -35,9 +50,10 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_f32(GroupArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// force_mt != 0: row tiles of 16 * force_mt rows whatever the jobs' sizes
 template <typename Launch>
 static hipError_t launch_groups(const Problem *p, uint32_t n, uint32_t tn, uint32_t m_small,
-                                uint32_t m_mid, Launch launch, uint64_t *launches)
+                                uint32_t m_mid, Launch launch, uint64_t *launches, int force_mt = 0)
 {
     for (uint32_t at = 0; at < n; at += kMaxProblems) {
         GroupArgs a{};
@@ -47,7 +63,7 @@ static hipError_t launch_groups(const Problem *p, uint32_t n, uint32_t tn, uint3
             a.p[i] = p[at + i];
             max_m = std::max(max_m, a.p[i].M);
         }
-        const int mt = max_m <= m_small ? 1 : max_m <= m_mid ? 2 : 4;
+        const int mt = force_mt ? force_mt : max_m <= m_small ? 1 : max_m <= m_mid ? 2 : 4;
         const uint32_t tm = 16u * mt;
         uint64_t tiles = 0;
         for (uint32_t i = 0; i < a.n; ++i)
@@ -69,6 +85,7 @@ static hipError_t launch_groups(const Problem *p, uint32_t n, uint32_t tn, uint3
 // weights in L2, which measured faster than a half-empty 128-row tile.
 constexpr uint32_t kTiledAlways = 128, kTiledMaybe = 65;
 constexpr uint64_t kTiledMinGrid = 256;
+constexpr uint64_t kFullGrid = 256;      // one workgroup per compute unit
 
 hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipStream_t stream,
                                uint64_t *launches)
@@ -89,26 +106,59 @@ hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipSt
             return launch_grouped_bf16(streamed.data(), (uint32_t)streamed.size(), false, stream, launches);
         }
     }
-    auto launch = [&](int mt, const GroupArgs &a, uint32_t tiles) {
+    // Up to 32 rows: one row tile of 16 or 32 rows per job, 128 columns, every weight
+    // read once (non-temporal).  33 .. 128 rows (those the tiled kernel did not take):
+    // when 64-row tiles of 128 columns would not even make one workgroup per compute
+    // unit (a few training jobs, say), row tiles of 64 rows and 64 columns: twice the
+    // workgroups, and the weights pass through a compute unit's memory path once per
+    // 64 rows (2048 x 2048 layers of 8 jobs at 64 rows: 21.0 us against 22.7 us
+    // forward, 21.4 against 28.2 us for the input gradient, whose rows are then read
+    // in whole cache lines).  With enough jobs to fill the chip, and above 128 rows,
+    // 32-row tiles of 128 columns as before: there the 64-row variants lose (64 jobs
+    // of 2048 x 2048 at 64 rows: 137 us with two 32-row tiles, 123 us with one
+    // 64 x 128 tile, 142 us with 64 x 64 tiles; but on the 1024-deep layers of the
+    // inference models the 64 x 128 tile, at one workgroup per compute unit, was 5 %
+    // slower than two 32-row tiles, which overlap each other's start and end).
+    std::vector<Problem> small, mid, large;
+    for (uint32_t i = 0; i < n; ++i)
+        (p[i].M <= 32 ? small : p[i].M <= 128 ? mid : large).push_back(p[i]);
+    auto launch_wide = [&](int mt, const GroupArgs &a, uint32_t tiles) {
         const dim3 grid(tiles), block(kGemmThreads);
-        // mt == 1 means no job has more than 16 rows; with mt == 2 a job above 32
-        // rows has several row tiles that read the same weights
-        bool one_row_tile = true;
+        bool one_row_tile = true;      // else several row tiles read the same weights: plain loads, L2 serves the others
         for (uint32_t i = 0; i < a.n; ++i) one_row_tile = one_row_tile && a.p[i].M <= 16u * mt;
-        if (trans_w) {
-            if (mt == 1) hipLaunchKernelGGL((grouped_dense_bf16<1, true, true>), grid, block, 0, stream, a);
-            else if (one_row_tile) hipLaunchKernelGGL((grouped_dense_bf16<2, true, true>), grid, block, 0, stream, a);
-            else hipLaunchKernelGGL((grouped_dense_bf16<2, true, false>), grid, block, 0, stream, a);
-        } else {
-            if (mt == 1) hipLaunchKernelGGL((grouped_dense_bf16<1, false, true>), grid, block, 0, stream, a);
-            else if (one_row_tile) hipLaunchKernelGGL((grouped_dense_bf16<2, false, true>), grid, block, 0, stream, a);
-            else hipLaunchKernelGGL((grouped_dense_bf16<2, false, false>), grid, block, 0, stream, a);
-        }
+#define SALUS_WIDE(MT_)                                                                                        \
+        do {                                                                                                    \
+            if (trans_w && one_row_tile) hipLaunchKernelGGL((grouped_dense_bf16<MT_, true, true>), grid, block, 0, stream, a);   \
+            else if (trans_w) hipLaunchKernelGGL((grouped_dense_bf16<MT_, true, false>), grid, block, 0, stream, a);            \
+            else if (one_row_tile) hipLaunchKernelGGL((grouped_dense_bf16<MT_, false, true>), grid, block, 0, stream, a);       \
+            else hipLaunchKernelGGL((grouped_dense_bf16<MT_, false, false>), grid, block, 0, stream, a);                        \
+        } while (0)
+        if (mt == 1) SALUS_WIDE(1);
+        else SALUS_WIDE(2);
+#undef SALUS_WIDE
     };
-    // Row tiles of at most 32 rows: a 64-row tile halves the workgroup count and
-    // the occupancy, and measured slower even though W is then read once instead
-    // of twice (the second read of neighbouring row tiles hits L2).
-    return launch_groups(p, n, 128, 16, 1u << 30, launch, launches);
+    auto launch_n64 = [&](int, const GroupArgs &a, uint32_t tiles) {
+        const dim3 grid(tiles), block(kGemmThreads);
+        bool one_row_tile = true;
+        for (uint32_t i = 0; i < a.n; ++i) one_row_tile = one_row_tile && a.p[i].M <= 64u;
+        if (trans_w && one_row_tile) hipLaunchKernelGGL((grouped_dense_bf16_n64<true, true>), grid, block, 0, stream, a);
+        else if (trans_w) hipLaunchKernelGGL((grouped_dense_bf16_n64<true, false>), grid, block, 0, stream, a);
+        else if (one_row_tile) hipLaunchKernelGGL((grouped_dense_bf16_n64<false, true>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((grouped_dense_bf16_n64<false, false>), grid, block, 0, stream, a);
+    };
+    if (!small.empty())
+        if (hipError_t e = launch_groups(small.data(), (uint32_t)small.size(), 128, 16, 32, launch_wide, launches)) return e;
+    if (!mid.empty()) {
+        uint64_t wide_tiles = 0;
+        for (const Problem &q : mid) wide_tiles += (uint64_t)((q.M + 63) / 64) * ((q.N + 127) / 128);
+        hipError_t e = wide_tiles >= kFullGrid
+                           ? launch_groups(mid.data(), (uint32_t)mid.size(), 128, 0, 0, launch_wide, launches, 2)
+                           : launch_groups(mid.data(), (uint32_t)mid.size(), 64, 0, 0, launch_n64, launches, 4);
+        if (e != hipSuccess) return e;
+    }
+    if (!large.empty())
+        if (hipError_t e = launch_groups(large.data(), (uint32_t)large.size(), 128, 0, 0, launch_wide, launches, 2)) return e;
+    return hipSuccess;
 }
 
 hipError_t launch_grouped_f32(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches)

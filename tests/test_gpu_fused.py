@@ -67,7 +67,7 @@ def test_jobs_the_fused_launch_does_not_take_fall_back_to_one_launch_per_depth()
     # 40 rows (bf16) is above what the weight-streaming kernels are used for;
     # seven layers are more than one fused launch holds
     for jobs, launches in [([dict(M=40, dims=(64, 72, 40), acts=[RELU, NONE]),
-                             dict(M=4, dims=(64, 72, 40), acts=[RELU, NONE])], 2),
+                             dict(M=4, dims=(64, 72, 40), acts=[RELU, NONE])], 4),   # per depth: up to 32 rows, above
                            ([dict(M=3, dims=(64,) * 8, acts=[RELU] * 6 + [NONE])], 7)]:
         outs, refs, fused_launches, plain_launches = both_ways(jobs, salus.BF16)
         assert fused_launches == plain_launches == launches

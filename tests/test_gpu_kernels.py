@@ -139,16 +139,34 @@ def run_jobs(jobs, dtype, fuse=False):
 GELU, RELU, NONE = salus.ACT_GELU, salus.ACT_RELU, salus.ACT_NONE
 
 
-@pytest.mark.parametrize("M", [1, 5, 16, 17, 32, 33, 64, 70])
+@pytest.mark.parametrize("M", [1, 5, 16, 17, 32, 33, 48, 64, 65, 70, 96, 127, 128])
 def test_bf16_single_layer_ragged_shapes(M):
     jobs = [dict(M=M, dims=(K, N), acts=[act]) for K, N, act in
             [(8, 8, NONE), (40, 72, RELU), (136, 136, GELU), (1024, 520, NONE), (264, 128, GELU),
              (32, 1000, NONE)]]
     outs, refs, launches = run_jobs(jobs, salus.BF16)
-    assert launches == 1
+    assert launches == (1 if M < 128 else 2)      # from 128 rows the layer with K % 64 == 0 goes to the tiled kernel
     for o, r, j in zip(outs, refs, jobs):
         assert np.isfinite(o).all(), j
         assert norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
+
+
+@pytest.mark.parametrize("M", [33, 64, 65, 128])
+def test_bf16_rows_33_to_128_take_64_row_tiles_of_either_width(M):
+    """Few jobs: 64-column tiles (more workgroups); many jobs: 128-column tiles.  Both
+    read the weights once per 64 rows; ragged K, N and strips included."""
+    shapes = [(72, 8, NONE), (136, 200, RELU), (1000, 520, GELU), (2048, 1000, NONE), (264, 128, GELU)]
+    few = [dict(M=M, dims=(K, N), acts=[act]) for K, N, act in shapes]
+    few.append(dict(M=M, dims=(256, 512, 384, 136), acts=[GELU, RELU, NONE], strip=True))
+    outs, refs, launches = run_jobs(few, salus.BF16)
+    for o, r, j in zip(outs, refs, few):
+        assert np.isfinite(o).all(), j
+        assert norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
+    many = [dict(M=max(M - (i % 3), 33), dims=(40, 1000), acts=[[NONE, RELU, GELU][i % 3]]) for i in range(40)]
+    outs, refs, launches = run_jobs(many, salus.BF16)           # 40 jobs x 8 column tiles >= 256
+    assert launches == 1
+    for o, r, j in zip(outs, refs, many):
+        assert np.isfinite(o).all() and norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
 
 
 def test_bf16_mixed_batch_sizes_and_depths_in_one_packed_iteration():
@@ -171,7 +189,7 @@ def test_bf16_jobs_with_many_rows_take_the_tiled_kernel(M):
     jobs.append(dict(M=5, dims=(192, 264), acts=[GELU]))         # small job of the same round
     jobs.append(dict(M=M, dims=(40, 72), acts=[RELU]))           # K not a multiple of 64: streamed
     outs, refs, launches = run_jobs(jobs, salus.BF16)
-    assert launches == 2                                          # tiled + streaming, same layer depth
+    assert launches == 3                                          # tiled + streaming (small job, big job), same layer depth
     for o, r, j in zip(outs, refs, jobs):
         assert np.isfinite(o).all(), j
         assert norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))

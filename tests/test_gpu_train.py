@@ -118,6 +118,8 @@ def check_step_stagewise(job, Xb, labels):
         slack = np.spacing(np.abs(w0).max()) / float(job.lr)
         assert np.abs(g_gpu - g).max() < TOL_GRAD * gmax + 2 * slack, (job.job, "dW", l)
         assert np.array_equal(gWb[l], synth.f32_to_bf16_bits(wm_gpu)), (job.job, "Wb", l)
+    # continue from the GPU's weights so that errors do not compound across steps
+    job.Wm, job.Wb = gWm, gWb
 
 
 def check_step(job, Xb, labels, step, tol_grad=TOL_GRAD):
@@ -181,8 +183,10 @@ def run(configs, steps, seed, update_launches=1, extra_forward_launches=0):
 
 
 def test_train_step_ragged_shapes():
+    # jobs of up to 32 rows and jobs of 33 .. 128 rows take different kernels: where a
+    # depth holds both there are two launches (forward depths 0 and 1, first input gradient)
     run([((72, 136, 264, 40), 13, 0.05), ((264, 72, 8), 64, 0.01), ((40, 520, 136), 33, 0.1),
-         ((128, 128), 1, 0.02)], steps=2, seed=0)
+         ((128, 128), 1, 0.02)], steps=2, seed=0, extra_forward_launches=3)
 
 
 def test_more_update_problems_than_one_launch_holds():
@@ -201,7 +205,7 @@ def test_train_step_loss_kernel_paths():
     kernel), more than 1024 classes (rows re-read instead of kept in registers),
     exactly 1024, and both at once."""
     run([((72, 40), 70, 0.05), ((64, 1032), 9, 0.05), ((40, 72, 1024), 130, 0.01), ((136, 2056), 66, 0.02),
-         ((64, 8), 64, 0.1)], steps=1, seed=3)
+         ((64, 8), 64, 0.1)], steps=1, seed=3, extra_forward_launches=2)   # first depth: three row classes
 
 
 def test_train_step_lr_zero_changes_nothing():
@@ -236,8 +240,12 @@ def test_workload3_hyperparameter_tuning_scaled():
             j.put_batch(w["X"][k][step], w["labels"][k][step])
         assert dp.pool.grouped_train_step(descs, stream=dp.stream) == salus.OK
         dp.sync()
+        # 8 jobs x 64 rows x 3 hidden layers of 256 units over 3 steps: about one run in
+        # ten has a unit whose pre-activation lies within one float rounding of zero, and
+        # then the two sides would take its ReLU derivative differently; so every stage is
+        # checked on the activations the GPU stored (same decision on both sides)
         for k, j in enumerate(jobs):
-            check_step(j, w["X"][k][step], w["labels"][k][step], step)
+            check_step_stagewise(j, w["X"][k][step], w["labels"][k][step])
     dp.close()
 
 
