@@ -189,11 +189,13 @@ def main():
         sys.exit("bench.py needs a GPU")
     if args.train_only:
         torch.cuda.set_device(0)
-        print(json.dumps(training_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
+        print(json.dumps(training_figures(torch, salus, torch.cuda.current_stream().cuda_stream,
+                                          with_cpu=not args.no_cpu_baseline)))
         return
     if args.switch_only:
         torch.cuda.set_device(0)
-        print(json.dumps(switch_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
+        print(json.dumps(switch_figures(torch, salus, torch.cuda.current_stream().cuda_stream,
+                                        with_cpu=not args.no_cpu_baseline)))
         return
     if args.latency_only:
         torch.cuda.set_device(0)
@@ -246,7 +248,7 @@ def main():
                    "pct_of_bf16_mfma_peak": round(100 * main_res["tflops"] / MFMA_BF16_PEAK_TFLOPS, 3)},
         "roofline": {"bound": "hbm", "achieved": round(main_res["gbs"], 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(main_res["gbs"] / HBM_PEAK_GBS, 4),
-                     "traffic": profiled_traffic(K_steps, W_steps),
+                     "traffic": profiled_traffic(K_steps, W_steps, main_res["bytes_per_launch"]),
                      "kernel": "chained_dense" if fused else "grouped_dense_bf16",
                      "avg_launch_ms": round(main_res["kernel_ms_per_launch"], 5),
                      "algorithmic_bytes_per_launch": int(main_res["bytes_per_launch"])},
@@ -297,16 +299,32 @@ def main():
                                          f"({len(work)} model forwards, {cpu_flops / 2e9:.2f} GMAC), "
                                          f"{cpu_s:.1f} s wall on {cores} threads"}
         log(f"[cpu] {out['cpu_baseline']}")
+        # the same oracle on one thread: the first timed round (about a quarter of the work above)
+        single, rows_1 = [], 0
+        for item in work:
+            if rows_1 >= sum(b for _, b in work) // 4:
+                break
+            single.append(item)
+            rows_1 += item[1]
+        t0 = time.perf_counter()
+        for item in single:
+            one(item)
+        one_s = time.perf_counter() - t0
+        out["cpu_baseline_single_thread"] = {
+            "value": round(2.0 * mac_per_row * rows_1 / one_s / 1e12, 6), "unit": "TFLOP/s", "cores": 1,
+            "kind": "oracle", "sample": f"the first {len(single)} model forwards of the same rounds "
+                                        f"({mac_per_row * rows_1 / 1e9:.2f} GMAC), {one_s:.1f} s wall on 1 thread"}
+        log(f"[cpu 1 thread] {out['cpu_baseline_single_thread']}")
     pool.close()
     del buf
     torch.cuda.empty_cache()
 
     # ---------------------------------------------------------------- switch path
     if not args.no_switch and not args.hot_only:
-        out["switch"] = switch_figures(torch, salus, stream)
+        out["switch"] = switch_figures(torch, salus, stream, with_cpu=not args.no_cpu_baseline)
         out["switch"]["overlapped"] = overlap_figures(torch, salus, stream)
     if not args.no_training and not args.hot_only:
-        out["training"] = training_figures(torch, salus, stream)
+        out["training"] = training_figures(torch, salus, stream, with_cpu=not args.no_cpu_baseline)
     if not args.hot_only:
         out["small_case_latency"] = latency_figures(torch, salus, synth, stream)
     if not args.no_sweep and not args.hot_only:
@@ -327,7 +345,7 @@ def main():
 
 
 def training_figures(torch, salus, stream, jobs=8, dims=(2048, 2048, 2048, 2048, 1000), M=64,
-                     steps=50, warmup=5):
+                     steps=50, warmup=5, with_cpu=True):
     """Hyper-parameter-tuning packing: 8 training jobs of one architecture, one
     packed step = schedule + forward + loss + backward + SGD for all of them."""
     up = lambda v: (v + 255) // 256 * 256
@@ -390,7 +408,49 @@ def training_figures(torch, salus, stream, jobs=8, dims=(2048, 2048, 2048, 2048,
            "launches_per_step": 9, "loss_job0_after": round(loss, 4)}
     log(f"[training] {res}")
     pool.close()
+    del buf
+    if with_cpu:
+        res.update(training_cpu_baseline(dims, M, jobs))
     return res
+
+
+def training_cpu_baseline(dims, M, jobs):
+    """The oracle's training step (oracle/train.py as it stands) on the host: one
+    job-step on one thread, then one step of all jobs on a thread per job."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import dense, train
+    from paper_1902_04610_amd import synth
+    dense.lib()
+    rng = np.random.Generator(np.random.PCG64(2))
+    params = sum(k * n for k, n in zip(dims[:-1], dims[1:]))
+    flops = 2.0 * M * (3 * params - dims[0] * dims[1])
+
+    def make():
+        Wm = [(rng.standard_normal((k, n), dtype=np.float32) * np.float32(1 / np.sqrt(k)))
+              for k, n in zip(dims[:-1], dims[1:])]
+        Wb = [synth.f32_to_bf16_bits(w) for w in Wm]
+        X = synth.f32_to_bf16_bits(rng.standard_normal((M, dims[0]), dtype=np.float32))
+        y = rng.integers(0, dims[-1], M).astype(np.int32)
+        return X, y, Wm, Wb
+
+    state = [make() for _ in range(jobs)]
+    t0 = time.perf_counter()
+    train.train_step(*state[0], 1e-3)
+    one_s = time.perf_counter() - t0
+    cores = min(jobs, os.cpu_count() or 1)
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        list(ex.map(lambda st: train.train_step(*st, 1e-3), state))
+    all_s = time.perf_counter() - t0
+    out = {"cpu_baseline_single_thread": {"value": round(flops / one_s / 1e12, 6), "unit": "TFLOP/s", "cores": 1,
+                                          "kind": "oracle", "sample": f"one job-step ({flops / 1e9:.2f} GFLOP), "
+                                                                      f"{one_s:.1f} s wall"},
+           "cpu_baseline": {"value": round(jobs * flops / all_s / 1e12, 6), "unit": "TFLOP/s", "cores": cores,
+                            "kind": "oracle", "sample": f"one packed step of all {jobs} jobs, a thread per job, "
+                                                        f"{all_s:.1f} s wall"}}
+    log(f"[training cpu] {out}")
+    return out
 
 
 def sweep_figures(torch, salus, stream, batches=(32, 48, 64, 80, 96, 112, 128, 256, 512, 1024, 2048, 4096)):
@@ -468,21 +528,24 @@ def layer_list(salus):
                                         (salus.ACT_GELU, salus.ACT_GELU, salus.ACT_NONE))]
 
 
-def profiled_traffic(steps, warmup):
+def profiled_traffic(steps, warmup, algorithmic_bytes_per_launch):
     """HBM bytes per launch of the dominant kernel as the profiler's counters saw
-    them (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size), taken from the
-    committed summary of the same workload; None if that summary was made with
-    other --steps / --warmup than this run."""
+    them (FETCH_SIZE + WRITE_SIZE, each scaled by a copy of known size), taken from
+    the committed summary of the same workload.  The summary holds one line per
+    profiled command (--steps / --warmup); a run with other values gets the
+    summary's counted / algorithmic ratio applied to its own algorithmic bytes."""
     path = os.path.join(ROOT, "profiles", "grouped_dense_bf16_inference_packing.txt")
+    ratio = None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
                 f = dict(kv.split("=") for kv in line.split()[1:])
                 if int(f["steps"]) == steps and int(f["warmup"]) == warmup:
                     return int(f["bytes"])
+                ratio = int(f["bytes"]) / float(f["algorithmic"]) if "algorithmic" in f else ratio
     except (OSError, KeyError, ValueError):
         pass
-    return None
+    return None if ratio is None else int(ratio * algorithmic_bytes_per_launch)
 
 
 def latency_figures(torch, salus, synth, stream, rounds=2000, fused=False):
@@ -639,19 +702,34 @@ def overlap_figures(torch, salus, stream, blob_gb=8, batch=MAX_BATCH):
     return res
 
 
-def switch_figures(torch, salus, stream):
-    """Evict / restore of one 4 GB job over the host link with both engines and
-    sliding compaction of 24 GB of persistent blocks (best of 3 each)."""
+def switch_figures(torch, salus, stream, with_cpu=True):
+    """The job-switch path at the sizes of the priority-preemption and
+    fragmentation workloads: evict / restore of a 20 GB job over the host link with
+    both engines (best of 2 after the repetition that allocates the pinned buffer),
+    and on-device compaction on four plans, each verified with the device pattern:
+    three 8 GB blocks that move by their own length (independent segments), one
+    8 GB block that moves by 256 bytes and one that moves by 40 MiB (both overlap
+    their own destination: the in-place kernel), and the forced compaction of the
+    fragmentation workload (about 200 GB of blocks drawn from its size distribution,
+    a seeded random half freed).  ms/GB counts GB = 1e9 bytes of payload moved;
+    HBM traffic = read + write = 2 x payload."""
+    import numpy as np
     GB = 10 ** 9
     res = {}
-    P = 4 * GB // 256 * 256
+    scratch = torch.zeros(8, dtype=torch.uint8, device="cuda:0")
+
+    def verify(buf, off, nbytes, seed):
+        return salus.check_pattern(buf.data_ptr() + off, nbytes // 8 * 8, seed, scratch.data_ptr(), stream)
+
+    P = 20 * GB // 256 * 256
     for name, engine in (("kernel", salus.COPY_KERNEL), ("dma", salus.COPY_DMA)):
+        torch.cuda.empty_cache()
         buf = torch.empty(P + 2 * MiB, dtype=torch.uint8, device="cuda:0")
         pool = salus.Pool(buf.data_ptr(), P + 2 * MiB, stream=stream, copy_engine=engine)
         st, j = pool.lane_alloc(P, MiB, 0, 1)
         salus.fill_pattern(buf.data_ptr(), P, 7, stream)
         out_ms, in_ms = [], []
-        for rep in range(4):                      # the first repetition allocates the pinned buffer
+        for rep in range(3):                      # the first repetition allocates the pinned buffer
             t0 = time.perf_counter()
             assert pool.switch_out(j) == salus.OK
             t1 = time.perf_counter()
@@ -660,43 +738,99 @@ def switch_figures(torch, salus, stream):
             if rep:
                 out_ms.append((t1 - t0) * 1e3)
                 in_ms.append((t2 - t1) * 1e3)
-        scratch = torch.zeros(8, dtype=torch.uint8, device="cuda:0")
-        q = pool.job_query(j)
-        assert salus.check_pattern(buf.data_ptr() + q.persist_off, P, 7, scratch.data_ptr(), stream) == 0
+        assert verify(buf, pool.job_query(j).persist_off, P, 7) == 0
         res[f"evict_{name}_ms_per_GB"] = round(min(out_ms) / (P / GB), 3)
         res[f"restore_{name}_ms_per_GB"] = round(min(in_ms) / (P / GB), 3)
         res[f"evict_{name}_GBs"] = round(P / GB / (min(out_ms) * 1e-3), 2)
         res[f"restore_{name}_GBs"] = round(P / GB / (min(in_ms) * 1e-3), 2)
         pool.close()
         del buf
+    res["switch_bytes_per_call"] = P
+
+    def timed_compaction(sizes, free, cap, reps, label):
+        """Blocks of `sizes` bytes are placed in order, those listed in `free` leave, then compact()."""
         torch.cuda.empty_cache()
-    # compaction: [hole 8 GB][3 blocks of 8 GB] -> slide 24 GB down by 8 GB
+        buf = torch.empty(cap, dtype=torch.uint8, device="cuda:0")
+        best, moved, launches = None, 0, 0
+        for rep in range(reps):
+            pool = salus.Pool(buf.data_ptr(), cap, stream=stream, max_lanes=1)
+            ids = [pool.lane_alloc(sz, MiB, 0, 1)[1] for sz in sizes]
+            keep = [k for k in range(len(sizes)) if k not in free]
+            for k in keep:
+                salus.fill_pattern(buf.data_ptr() + pool.job_query(ids[k]).persist_off, sizes[k] // 8 * 8, 100 + k, stream)
+            for k in free:
+                pool.lane_free(ids[k])
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            plan = pool.compact()
+            dt = time.perf_counter() - t0
+            moved = sum(m[2] for m in plan)
+            for k in keep:
+                assert verify(buf, pool.job_query(ids[k]).persist_off, sizes[k], 100 + k) == 0, (label, k)
+            best = dt if best is None else min(best, dt)
+            pool.close()
+        del buf
+        out = {"ms_per_GB_moved": round(best * 1e3 / (moved / GB), 4),
+               "hbm_GBs_read_plus_write": round(2 * moved / best / 1e9, 1),
+               "hbm_frac": round(2 * moved / best / 1e9 / HBM_PEAK_GBS, 4),
+               "bytes_moved": moved, "moves": len(plan)}
+        log(f"[compact {label}] {out}")
+        return out
+
     blk = 8 * GB // 256 * 256
-    cap = 4 * blk + 2 * MiB
-    buf = torch.empty(cap, dtype=torch.uint8, device="cuda:0")
-    best = None
-    for rep in range(3):
-        pool = salus.Pool(buf.data_ptr(), cap, stream=stream, max_lanes=1)
-        ids = [pool.lane_alloc(blk, MiB, 0, 1)[1] for _ in range(4)]
-        for k in (1, 2, 3):
-            salus.fill_pattern(buf.data_ptr() + pool.job_query(ids[k]).persist_off, blk, 100 + k, stream)
-        pool.lane_free(ids[0])
-        torch.cuda.synchronize()
+    indep = timed_compaction([blk] * 4, {0}, 4 * blk + 2 * MiB, 3, "independent 3 x 8 GB")
+    res["compact_ms_per_GB_moved"] = indep["ms_per_GB_moved"]
+    res["compact_hbm_GBs_read_plus_write"] = indep["hbm_GBs_read_plus_write"]
+    res["compact_hbm_frac"] = indep["hbm_frac"]
+    res["compact_bytes_moved"] = indep["bytes_moved"]
+    res["compact_shift_256B"] = timed_compaction([256, blk], {0}, blk + 256 + 2 * MiB, 3, "8 GB by 256 B (in place)")
+    res["compact_shift_40MiB"] = timed_compaction([40 * MiB, blk], {0}, blk + 42 * MiB, 3, "8 GB by 40 MiB (in place)")
+    # forced compaction of the fragmentation workload
+    rng = np.random.Generator(np.random.PCG64(44))
+    sizes, total = [], 0
+    while True:
+        sz = int(rng.lognormal(np.log(1e9), 0.8)) // 256 * 256 + 256
+        if total + sz > 200 * GB:
+            break
+        sizes.append(sz)
+        total += sz
+    free = set(int(k) for k in rng.permutation(len(sizes))[:len(sizes) // 2])
+    forced = timed_compaction(sizes, free, 204 * GB // 256 * 256, 1, f"forced, {len(sizes)} blocks, {total / 1e9:.0f} GB")
+    forced["blocks"] = len(sizes)
+    res["compact_forced_200GB"] = forced
+    torch.cuda.empty_cache()
+
+    if with_cpu:
+        # the oracle's switch is a memcpy out of and into its byte array: timed on a 2 GB job
+        from oracle import pool as op
+        n = 2 * GB // 256 * 256
+        mem = np.zeros(n + MiB, np.uint8)
+        o = op.Pool(n + MiB, mem=mem)
+        o.job_arrive(n, MiB // 2)
+        mem[:n:4096] = 1                              # touch the pages
         t0 = time.perf_counter()
-        plan = pool.compact()
-        dt = time.perf_counter() - t0
-        moved = sum(m[2] for m in plan)
-        scratch = torch.zeros(8, dtype=torch.uint8, device="cuda:0")
-        for k in (1, 2, 3):
-            assert salus.check_pattern(buf.data_ptr() + pool.job_query(ids[k]).persist_off, blk, 100 + k,
-                                       scratch.data_ptr(), stream) == 0
-        best = dt if best is None else min(best, dt)
-        pool.close()
-    res["compact_ms_per_GB_moved"] = round(best * 1e3 / (moved / GB), 4)
-    res["compact_hbm_GBs_read_plus_write"] = round(2 * moved / best / 1e9, 1)
-    res["compact_hbm_frac"] = round(2 * moved / best / 1e9 / HBM_PEAK_GBS, 4)
-    res["compact_bytes_moved"] = moved
-    log(f"[switch] {res}")
+        assert o.switch_out(0) == op.OK
+        t1 = time.perf_counter()
+        assert o.switch_in(0) == op.OK
+        t2 = time.perf_counter()
+        res["cpu_baseline"] = {"evict_ms_per_GB": round((t1 - t0) * 1e3 / (n / GB), 2),
+                               "restore_ms_per_GB": round((t2 - t1) * 1e3 / (n / GB), 2),
+                               "unit": "ms/GB", "cores": 1, "kind": "oracle",
+                               "sample": "switch_out + switch_in of a 2 GB job in the oracle's host byte array "
+                                         "(a tenth of the 20 GB job)"}
+        # and its compaction plan for the forced case (metadata only: no host mirror of 200 GB exists)
+        o = op.Pool(204 * GB // 256 * 256, max_lanes=1)
+        for sz in sizes:
+            o.job_arrive(sz, MiB)
+        for k in sorted(free):
+            o.job_finish(k)
+        t0 = time.perf_counter()
+        plan = o.compact()
+        res["cpu_baseline"]["forced_plan_ms"] = round((time.perf_counter() - t0) * 1e3, 3)
+        res["cpu_baseline"]["forced_plan_moves"] = len(plan)
+        assert sum(m[2] for m in plan) == forced["bytes_moved"]
+        log(f"[switch cpu] {res['cpu_baseline']}")
+    log(f"[switch] { {k: v for k, v in res.items() if not isinstance(v, dict)} }")
     return res
 
 

@@ -16,10 +16,13 @@
  *  - "device pointer" = address valid on the GPU; "host pointer" = ordinary
  *    process memory.  All sizes and offsets are bytes (uint64_t); offsets are
  *    relative to the pool base.
- *  - The library places nothing in device memory of its own, with one exception:
- *    a pool created with SALUS_FLAG_FUSE_DEPTHS holds about 20 KB for descriptors
- *    and completion counters.  It owns its metadata and the pinned host buffers
- *    that hold evicted state (unless the caller passes one).
+ *  - The library keeps almost nothing in device memory of its own: every pool with
+ *    device memory holds 16 KB of counters for in-place compaction, a pool created
+ *    with SALUS_FLAG_FUSE_DEPTHS another 20 KB for descriptors and completion
+ *    counters (both allocated in salus_pool_create, never later), and
+ *    salus_grouped_forward_static uses a fixed array inside the library.  It owns
+ *    its metadata and the pinned host buffers that hold evicted state (unless the
+ *    caller passes one).
  *  - Not thread safe: one scheduler thread drives a pool (the paper's execution
  *    service is a singleton, Section 3.1).
  *  - Calls that change the layout (lane_alloc, lane_free, switch_out, switch_in,
@@ -363,9 +366,10 @@ int32_t salus_switch_in_end(salus_pool_t *pool, int32_t job, int32_t wait);
  * move-back scheme costly; it never moves persistent memory and does not say
  * how that region is allocated.  Reading taken: slide all live persistent
  * blocks to the low end in address order; new offset = exclusive prefix sum of
- * the granule-rounded sizes.  Executes the moves on the device (overlap-safe;
- * staging, if any, only in the unused gap between the highest live block and
- * the lanes, so lane contents survive) and writes the plan to
+ * the granule-rounded sizes.  Executes the moves on the device, each byte read
+ * once and written once, in place also where a block overlaps its own
+ * destination (no staging: nothing outside the moved blocks is touched, lane
+ * contents survive) and writes the plan to
  * plan_out[0..*n_moves) in ascending source order (at most cap entries are
  * written; *n_moves is the full count).  Blocks that already sit at their
  * final offset do not appear.  lane_alloc, switch_in and switch_in_begin run the

@@ -26,6 +26,7 @@ struct HipOps : DeviceOps {
     int engine = SALUS_COPY_KERNEL;
     std::string *error = nullptr;
     uint64_t copy_launches = 0;
+    SlideState slide_state;                 // counters of the in-place compaction kernel (16 KB on the device)
     // transfers begun and not yet ended (job id -> fence on the pool's stream, completion event)
     struct Transfer { hipEvent_t fence, done; bool failed; };
     std::map<int32_t, Transfer> inflight;
@@ -69,7 +70,7 @@ struct HipOps : DeviceOps {
     {
         return host_copy(base + off, host, n, hipMemcpyHostToDevice);
     }
-    int slide(const salus_move *m, uint32_t n, uint64_t free_off, uint64_t free_len) override
+    int slide(const salus_move *m, uint32_t n) override
     {
         std::vector<uint64_t> s(n), d(n), l(n);
         for (uint32_t i = 0; i < n; ++i) { s[i] = m[i].src; d[i] = m[i].dst; l[i] = m[i].len; }
@@ -79,11 +80,15 @@ struct HipOps : DeviceOps {
             hipError_t w = hipStreamWaitEvent(stream, kv.second.done, 0);
             if (w != hipSuccess) return fail(w, "hipStreamWaitEvent");
         }
-        hipError_t e = launch_slide(base, s.data(), d.data(), l.data(), n, free_off, free_len,
-                                    stream, &copy_launches);
+        hipError_t e = launch_slide(base, s.data(), d.data(), l.data(), n, &slide_state, stream, &copy_launches);
         if (e != hipSuccess) return fail(e, "compaction launch");
-        e = hipStreamSynchronize(stream);
+        uint32_t gave_up = 0;
+        e = slide_state_failed(&slide_state, stream, &gave_up);       // synchronizes the stream
         if (e != hipSuccess) return fail(e, "hipStreamSynchronize");
+        if (gave_up) {
+            if (error) *error = "an in-place move gave up waiting for a neighbouring chunk: the persistent region is damaged";
+            return -1;
+        }
         return 0;
     }
     void *pinned_alloc(uint64_t n) override
@@ -175,8 +180,13 @@ int32_t salus_pool_create(void *base, uint64_t capacity, const salus_config *cfg
     p->granule = c.granule;
     p->core.reset(new PoolCore(capacity, c.granule, c.max_lanes, c.policy,
                                (c.flags & SALUS_FLAG_SHRINK_LANES) != 0, &p->ops));
+    if (base && slide_state_create(&p->ops.slide_state) != hipSuccess) {
+        delete p;
+        return SALUS_EHIP;
+    }
     if ((c.flags & SALUS_FLAG_FUSE_DEPTHS) && base) {
         if (chain_create(&p->chain) != hipSuccess) {
+            slide_state_destroy(&p->ops.slide_state);
             delete p;
             return SALUS_EHIP;
         }
@@ -198,6 +208,7 @@ int32_t salus_pool_destroy(salus_pool_t *pool)
         (void)hipDeviceSynchronize();         // no launch may still read the table
         chain_destroy(pool->chain);
     }
+    slide_state_destroy(&pool->ops.slide_state);
     delete pool;
     return SALUS_OK;
 }
@@ -883,8 +894,15 @@ int32_t salus_copy(void *dst, const void *src, uint64_t nbytes, void *stream)
         CopySeg seg{src, dst, nbytes};
         e = launch_copy(&seg, 1, s);
     } else if (dp < sp) {
+        // this self-check has no pool: its in-place moves share one process-wide set of
+        // counters, so overlapping calls of salus_copy must not run concurrently
+        static SlideState state;
+        if (!state.progress && slide_state_create(&state) != hipSuccess) return SALUS_EHIP;
         uint64_t so = (uint64_t)(sp - dp), zo = 0, len = nbytes;   // offsets relative to dst
-        e = launch_slide(dp, &so, &zo, &len, 1, 0, 0, s, nullptr);
+        e = launch_slide(dp, &so, &zo, &len, 1, &state, s, nullptr);
+        uint32_t gave_up = 0;
+        if (e == hipSuccess) e = slide_state_failed(&state, s, &gave_up);
+        if (e == hipSuccess && gave_up) return SALUS_ETIMEOUT;
     } else {
         return SALUS_EINVAL;    // moving upward with overlap is never needed by the pool
     }

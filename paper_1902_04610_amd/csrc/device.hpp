@@ -19,11 +19,23 @@ constexpr uint32_t kCopyChunk = 8 * 1024;   // bytes one workgroup moves per gri
 // segment's source); more than kMaxSeg segments are split over launches.
 hipError_t launch_copy(const CopySeg *segs, uint32_t n, hipStream_t stream);
 
-// memmove toward lower addresses inside one allocation: dst < src, any overlap.
-// bounce/bounce_len: a free device range usable as staging (may be empty).
+// Device state of the in-place slide kernel: one progress counter per resident
+// workgroup and a failure word (16 KB of device memory, allocated once).
+constexpr uint32_t kSlideMaxGrid = 4032;
+struct SlideState {
+    uint32_t *progress = nullptr;   // kSlideMaxGrid counters
+    uint32_t *failed = nullptr;     // set to 1 by a workgroup whose bounded wait ran out
+    uint32_t max_grid = 0;          // resident workgroups a launch may use (found at the first launch)
+};
+hipError_t slide_state_create(SlideState *st);
+void slide_state_destroy(SlideState *st);
+hipError_t slide_state_failed(SlideState *st, hipStream_t stream, uint32_t *out);
+
+// memmove toward lower addresses inside one allocation: moves in ascending order,
+// dst < src, any overlap of a move with itself.  Every byte is read once and
+// written once; nothing outside the moved ranges is touched.
 hipError_t launch_slide(char *base, const uint64_t *src, const uint64_t *dst, const uint64_t *len,
-                        uint32_t n, uint64_t bounce_off, uint64_t bounce_len, hipStream_t stream,
-                        uint64_t *launches);
+                        uint32_t n, SlideState *st, hipStream_t stream, uint64_t *launches);
 
 hipError_t launch_scan_u64(const uint64_t *dev_in, uint32_t n, uint64_t *dev_out, hipStream_t s);
 hipError_t launch_fill_pattern(void *dev, uint64_t nbytes, uint64_t seed, hipStream_t s);

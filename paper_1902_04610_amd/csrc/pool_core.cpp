@@ -116,14 +116,7 @@ int PoolCore::do_compact(std::vector<salus_move> *plan_out)
         next += j.P;
     }
     int rc = 0;
-    if (!plan.empty() && dev_->present()) {
-        const auto &top = *blocks_.rbegin();
-        // staging may only use the gap between the highest live block and the
-        // ephemeral region: lanes hold inputs and outputs that callers keep
-        // across rounds, and other lanes may be iterating during a switch_in
-        const uint64_t high = round_up(top.first + jobs_[top.second].P, 256), fl = floor();
-        rc = dev_->slide(plan.data(), (uint32_t)plan.size(), high, high < fl ? fl - high : 0);
-    }
+    if (!plan.empty() && dev_->present()) rc = dev_->slide(plan.data(), (uint32_t)plan.size());
     if (rc) { error = "device compaction failed"; return SALUS_EHIP; }
     for (const auto &kv : packed) jobs_[kv.second].off = kv.first;
     blocks_.swap(packed);

@@ -20,10 +20,11 @@ struct DeviceOps {
     virtual bool present() const = 0;                       // false: metadata-only pool
     virtual int evict(void *host, uint64_t off, uint64_t n) = 0;      // device -> host
     virtual int restore(uint64_t off, const void *host, uint64_t n) = 0;
-    // moves in ascending address order, every dst below its src; [free_off,
-    // free_off + free_len) is the unused gap between the highest live block and
-    // the ephemeral region and may be used as staging (possibly empty)
-    virtual int slide(const salus_move *moves, uint32_t n, uint64_t free_off, uint64_t free_len) = 0;
+    // moves in ascending address order, every dst below its src, a move may overlap
+    // its own destination; nothing outside the moved ranges may be touched (lanes
+    // hold inputs and outputs that callers keep across rounds, and other lanes may
+    // be iterating while a switch_in compacts)
+    virtual int slide(const salus_move *moves, uint32_t n) = 0;
     virtual void *pinned_alloc(uint64_t n) = 0;
     virtual void pinned_free(void *p) = 0;
 };
