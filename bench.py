@@ -173,6 +173,9 @@ def main():
                     help="only evict / restore / compaction (for profiling)")
     ap.add_argument("--latency-only", action="store_true", help="only the small-case latency, both launch modes")
     ap.add_argument("--train-only", action="store_true", help="only the packed training step (for profiling)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="only the calibration: one 2048 x 2048 bf16 layer of J jobs per launch, J = 2 .. 64, at 32 "
+                         "and 64 rows (how the streaming rate depends on the number of workgroups), and a plain copy")
     args = ap.parse_args()
     global STRIP
     STRIP = not args.row_major
@@ -187,6 +190,10 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if args.calibrate:
+        torch.cuda.set_device(0)
+        print(json.dumps(calibration_figures(torch, salus, torch.cuda.current_stream().cuda_stream)))
+        return
     if args.train_only:
         torch.cuda.set_device(0)
         print(json.dumps(training_figures(torch, salus, torch.cuda.current_stream().cuda_stream,
@@ -450,6 +457,62 @@ def training_cpu_baseline(dims, M, jobs):
                             "kind": "oracle", "sample": f"one packed step of all {jobs} jobs, a thread per job, "
                                                         f"{all_s:.1f} s wall"}}
     log(f"[training cpu] {out}")
+    return out
+
+
+def calibration_figures(torch, salus, stream, K=2048, N=2048, max_jobs=64, sets=3):
+    """What one launch of the weight-streaming kernel reaches as a function of its
+    size: J jobs, each one K x N bf16 layer, J = 2 .. 64, at 32 rows (128-column
+    tiles) and at 64 rows.  Weight sets rotate so that every launch reads HBM.
+    Context for the small launches of the training step; not a workload."""
+    up = lambda v: (v + 255) // 256 * 256
+    P = sets * K * N * 2
+    x_off, y_off = 0, up(64 * K * 2)
+    E = up(y_off + 64 * N * 4)
+    cap = max_jobs * (P + E)
+    buf = torch.empty(cap, dtype=torch.uint8, device="cuda:0")
+    buf.view(torch.bfloat16).normal_(0, 0.02)
+    pool = salus.Pool(buf.data_ptr(), cap, policy=salus.POLICY_PACK, stream=stream)
+    for m in range(max_jobs):
+        st, j = pool.lane_alloc(P, E, 0, 10 ** 9)
+        assert st == salus.OK and j == m
+    rows = []
+    for M in (32, 64):
+        for J in (2, 4, 8, 16, 32, 64):
+            descs = [salus.Pool.make_descs(dict(job=m, M=M, dtype=salus.BF16, x_off=x_off, y_off=y_off, h_off=0,
+                                                layers=[(K, N, s * K * N * 2, salus.ACT_RELU)]) for m in range(J))
+                     for s in range(sets)]
+            reps = 30
+            for s in range(sets):
+                assert pool.grouped_forward(descs[s][0], J, stream) == salus.OK, pool.last_error()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for r in range(reps):
+                assert pool.grouped_forward(descs[r % sets][0], J, stream) == salus.OK
+            b.record()
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / reps
+            tile_cols = 128 if M <= 32 or J * (N // 128) >= 256 else 64
+            wgs = J * (N // tile_cols) * (2 if M > 32 and tile_cols == 128 else 1)
+            rows.append({"rows": M, "jobs": J, "workgroups": wgs, "us_per_launch": round(us, 2),
+                         "weight_MB": round(J * K * N * 2 / 1e6, 1), "hbm_gbs": round(J * K * N * 2 / us / 1e3, 1)})
+            log(f"[calibrate] {rows[-1]}")
+    pool.close()
+    del buf
+    torch.cuda.empty_cache()
+    n = 8 << 30
+    cal = torch.empty(2 * n, dtype=torch.uint8, device="cuda:0")
+    best = None
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        salus.copy(cal.data_ptr(), cal.data_ptr() + n, n, stream)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    out = {"workload": f"calibration: one {K} x {N} bf16 layer of J jobs per launch; 8 GiB plain copy",
+           "launches": rows, "copy_GBs_read_plus_write": round(2 * n / best / 1e9, 1)}
+    log(f"[calibrate] copy {out['copy_GBs_read_plus_write']} GB/s read + write")
     return out
 
 

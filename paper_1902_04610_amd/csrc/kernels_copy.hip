@@ -101,7 +101,8 @@ hipError_t launch_copy(const CopySeg *segs, uint32_t n, hipStream_t stream)
 // Every byte is read once and written once, whatever the shift.
 //
 // The range is cut into chunks of kSlideChunk bytes, processed in ascending order
-// by a grid of resident workgroups (workgroup w takes chunks w, w + G, ...).  A
+// by a grid of G workgroups that all fit on the device at once (workgroup w takes
+// chunks w, w + G, ...).  A
 // workgroup loads its whole chunk into registers, publishes "chunk read", and
 // only then may write it.  The destination of chunk i covers source bytes of
 // chunks i - q - 1 and i - q (q = shift / chunk) and of no later chunk, so the
@@ -111,11 +112,16 @@ hipError_t launch_copy(const CopySeg *segs, uint32_t n, hipStream_t stream)
 // cache maintenance is needed: a relaxed device-scope counter per workgroup
 // (chunks read so far) is enough.
 //
-// The launch is cooperative: the runtime guarantees that all G workgroups are
-// resident together, so every wait ends.  The wait is bounded all the same; a
-// workgroup that gives up sets `*failed`, skips its write and carries on
-// publishing its reads, so that every wavefront exits.  The host then reports
-// the compaction as failed.
+// Why every wait ends: G is at most two workgroups per compute unit of a kernel
+// that fits at least that many (checked with the occupancy query), so the grid
+// fits the device by itself; workgroups of other kernels that happen to run end
+// on their own, so all G workgroups become resident, and from then on the lowest
+// unwritten chunk never waits for anything that is not already under way.  (A
+// cooperative launch would have the runtime check the same fit; it is not used
+// because the profiler of this ROCm release crashes at exit after one.)  The wait
+// is bounded all the same; a workgroup that gives up sets `*failed`, skips its
+// write and carries on publishing its reads, so that every wavefront exits.  The
+// host then reports the compaction as failed.
 // ---------------------------------------------------------------------------
 // measured on MI355X, 8 GB moved down by 256 B / 48 KiB / 40 MiB (read + write): chunks of 32 KiB 5.3 / 5.2 / 5.3 TB/s,
 // 64 KiB 5.5 / 5.5 / 5.3, 128 KiB 5.65 / 5.65 / 5.36; two, four or eight workgroups per compute unit: no difference
@@ -203,10 +209,9 @@ static hipError_t launch_slide_down(char *dst, const char *src, uint64_t len, Sl
     hipLaunchKernelGGL(slide_reset, dim3(1), dim3(256), 0, stream, st->progress, grid, st->failed);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    uint32_t *progress = st->progress, *failed = st->failed;
-    uint32_t limit = kSlideSpinLimit;
-    void *args[] = {&dst, &src, &len, &progress, &failed, &limit};
-    return hipLaunchCooperativeKernel((const void *)slide_down, dim3(grid), dim3(kCopyThreads), args, 0, stream);
+    hipLaunchKernelGGL(slide_down, dim3(grid), dim3(kCopyThreads), 0, stream, dst, (const char *)src, len,
+                       st->progress, st->failed, kSlideSpinLimit);
+    return hipGetLastError();
 }
 
 hipError_t slide_state_create(SlideState *st)
