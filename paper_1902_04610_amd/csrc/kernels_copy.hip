@@ -124,8 +124,9 @@ hipError_t launch_copy(const CopySeg *segs, uint32_t n, hipStream_t stream)
 // host then reports the compaction as failed.
 // ---------------------------------------------------------------------------
 // measured on MI355X, 8 GB moved down by 256 B / 48 KiB / 40 MiB (read + write): chunks of 32 KiB 5.3 / 5.2 / 5.3 TB/s,
-// 64 KiB 5.5 / 5.5 / 5.3, 128 KiB 5.65 / 5.65 / 5.36; two, four or eight workgroups per compute unit: no difference
-constexpr uint32_t kSlideChunk = 128 * 1024;
+// 64 KiB 5.5 / 5.5 / 5.3, 128 KiB 5.7 / 5.7 / 5.4, 192 KiB 5.9 / 5.9 / 5.8, 256 KiB 5.9 / 5.9 / 5.5 (192 KiB is
+// 192 registers per lane, two workgroups per compute unit); more workgroups per compute unit: no difference
+constexpr uint32_t kSlideChunk = 192 * 1024;
 constexpr int kSlideVec = kSlideChunk / (kCopyThreads * 16);
 constexpr uint32_t kSlideSpinLimit = 1u << 22;      // polls of a microsecond or two each: seconds
 

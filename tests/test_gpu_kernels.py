@@ -41,10 +41,10 @@ def test_copy_disjoint(nbytes):
 
 @pytest.mark.parametrize("shift,nbytes", [(16, 4096), (256, 3 * 1024 * 1024 + 4096), (65536, 20 * 65536 + 48),
                                            (1 << 20, 9 * (1 << 20) + 512), (100 * 65536, 100 * 65536),
-                                           # the in-place kernel's chunks are 128 KiB: shifts around one and
+                                           # the in-place kernel's chunks are 192 KiB: shifts around one and
                                            # several chunks, and ranges of several rounds of its resident grid
-                                           (131072 + 16, 7 * 131072 + 32), (3 * 131072 - 16, 50 * 131072), (131072 - 16, 131072 + 16),
-                                           (131072, 9 * 131072 + 4096), (48 * 1024, 300 * (1 << 20) + 4080),
+                                           (196608 + 16, 7 * 196608 + 32), (3 * 196608 - 16, 50 * 196608), (196608 - 16, 196608 + 16),
+                                           (196608, 9 * 196608 + 4096), (131072, 9 * 131072 + 4096), (48 * 1024, 300 * (1 << 20) + 4080),
                                            (5 * (1 << 20) + 256, 200 * (1 << 20))])
 def test_copy_overlapping_toward_lower_addresses(shift, nbytes):
     rng = np.random.default_rng(shift)
