@@ -264,7 +264,9 @@ int32_t salus_grouped_forward(salus_pool_t *pool, const salus_gemm_desc *descs, 
  * by every pool and every call on that GPU and never cleared (every element
  * that is read was written earlier in the same call): calls that can overlap on
  * one GPU - different streams, or different host threads - race on it and must
- * be ordered by the caller.  The GPU of the pool must be the current device. */
+ * be ordered by the caller.  The GPU of the pool must be the current device.
+ * The first call on a device looks up the array's address; make one call (n = 0
+ * will do) before recording the entry point into a graph. */
 #define SALUS_STATIC_SCRATCH_BYTES (32ull << 20)
 int32_t salus_grouped_forward_static(salus_pool_t *pool, const salus_gemm_desc *descs, uint32_t n,
                                      void *stream);

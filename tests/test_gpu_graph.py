@@ -36,8 +36,11 @@ def test_the_fused_forward_refuses_to_be_recorded():
     dp.close()
 
 
-@pytest.mark.parametrize("dtype,fuse", [(salus.F32, False), (salus.BF16, False)])
-def test_a_recorded_round_replays_with_new_inputs(dtype, fuse):
+@pytest.mark.parametrize("dtype,fuse,static", [(salus.F32, False, False), (salus.BF16, False, False),
+                                               (salus.F32, False, True), (salus.BF16, False, True)])
+def test_a_recorded_round_replays_with_new_inputs(dtype, fuse, static):
+    """static: the entry point that keeps the hidden activations in the library's
+    own device array (what a caller under capture uses when it cannot allocate)."""
     esz = 4 if dtype == salus.F32 else 2
     dims, M, acts = (256, 256, 264), 8, [salus.ACT_RELU, salus.ACT_NONE]
     w_offs, P, x_off, y_off, h_off, E = mlp_layout(dims, esz, M)
@@ -81,12 +84,14 @@ def test_a_recorded_round_replays_with_new_inputs(dtype, fuse):
             ref = fwd(x, Ws, acts)[-1]
             assert norm_rel_err(y, ref) < (1e-5 if dtype == salus.F32 else 2e-3), (tag, jid)
 
+    forward = dp.pool.grouped_forward_static if static else dp.pool.grouped_forward
     side = torch.cuda.Stream()
     X = put_inputs()
     torch.cuda.synchronize()
     # one eager round on the side stream first (the fused path uploads its descriptors
-    # then, so that the recorded round holds the forward launch only)
-    assert dp.pool.grouped_forward(descs, stream=side.cuda_stream) == salus.OK
+    # then, so that the recorded round holds the forward launch only; the static variant
+    # looks up its array's address at its first call on a device)
+    assert forward(descs, stream=side.cuda_stream) == salus.OK
     side.synchronize()
     check(X, "eager")
 
@@ -94,7 +99,7 @@ def test_a_recorded_round_replays_with_new_inputs(dtype, fuse):
     X = put_inputs()
     torch.cuda.synchronize()
     with torch.cuda.graph(graph, stream=side):
-        assert dp.pool.grouped_forward(descs, stream=side.cuda_stream) == salus.OK
+        assert forward(descs, stream=side.cuda_stream) == salus.OK
     for replay in range(4):
         if replay:
             X = put_inputs()                       # eager copies between replays
