@@ -378,6 +378,16 @@ int32_t salus_switch_in_end(salus_pool_t *pool, int32_t job, int32_t wait);
  * same compaction by themselves when a request needs it. */
 int32_t salus_compact(salus_pool_t *pool, salus_move *plan_out, uint32_t cap, uint32_t *n_moves);
 
+/* An in-place move has workgroups wait for one another (a chunk is written only
+ * after the chunks under its destination have been read).  The wait is bounded:
+ * after `polls` polls (default 2^22, seconds) a workgroup gives up, skips its
+ * write and runs to its end, and the operation that needed the compaction
+ * returns SALUS_EHIP with "gave up" in salus_last_error; the persistent region
+ * is then damaged and the pool must be destroyed.  With the default this cannot
+ * happen on an otherwise idle device; the knob exists for tests of that path
+ * (polls = 0 gives up at the first unsuccessful poll). */
+int32_t salus_compact_spin_limit(salus_pool_t *pool, uint32_t polls);
+
 int32_t salus_get_stats(salus_pool_t *pool, salus_stats *out);
 /* Copies and clears the event log (at most cap entries; *n = entries copied). */
 int32_t salus_poll_events(salus_pool_t *pool, salus_event *out, uint32_t cap, uint32_t *n);

@@ -106,6 +106,7 @@ struct salus_pool {
     HipOps ops;
     std::unique_ptr<PoolCore> core;
     std::string error;
+    std::string device_error;               // written by the device layer underneath a pool operation
     uint64_t granule = 256;
     uint64_t gemm_launches = 0;
     Chain *chain = nullptr;                 // SALUS_FLAG_FUSE_DEPTHS: the depth-fused forward's device state
@@ -152,7 +153,12 @@ static int32_t set_error(salus_pool *p, int32_t code, const std::string &msg)
 
 static int32_t done(salus_pool *p, int32_t rc)
 {
-    if (rc < 0 && !p->core->error.empty()) p->error = p->core->error;
+    if (rc < 0 && !p->core->error.empty()) {
+        p->error = p->core->error;
+        // what the device layer said about the same failure is the more specific half
+        if (!p->device_error.empty()) p->error += " (" + p->device_error + ")";
+    }
+    p->device_error.clear();
     return rc;
 }
 
@@ -176,7 +182,7 @@ int32_t salus_pool_create(void *base, uint64_t capacity, const salus_config *cfg
     p->ops.capacity = capacity;
     p->ops.stream = (hipStream_t)c.stream;
     p->ops.engine = c.copy_engine;
-    p->ops.error = &p->error;
+    p->ops.error = &p->device_error;
     p->granule = c.granule;
     p->core.reset(new PoolCore(capacity, c.granule, c.max_lanes, c.policy,
                                (c.flags & SALUS_FLAG_SHRINK_LANES) != 0, &p->ops));
@@ -505,6 +511,13 @@ int32_t salus_fused_spin_limit(salus_pool_t *pool, uint32_t polls)
 {
     CHECK_POOL(pool);
     pool->spin_limit = polls;
+    return SALUS_OK;
+}
+
+int32_t salus_compact_spin_limit(salus_pool_t *pool, uint32_t polls)
+{
+    CHECK_POOL(pool);
+    pool->ops.slide_state.spin_limit = polls;
     return SALUS_OK;
 }
 

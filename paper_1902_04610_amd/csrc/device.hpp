@@ -26,6 +26,7 @@ struct SlideState {
     uint32_t *progress = nullptr;   // kSlideMaxGrid counters
     uint32_t *failed = nullptr;     // set to 1 by a workgroup whose bounded wait ran out
     uint32_t max_grid = 0;          // resident workgroups a launch may use (found at the first launch)
+    uint32_t spin_limit = 1u << 22; // polls (a microsecond or two each) before a wait gives up: seconds
 };
 hipError_t slide_state_create(SlideState *st);
 void slide_state_destroy(SlideState *st);

@@ -128,12 +128,11 @@ hipError_t launch_copy(const CopySeg *segs, uint32_t n, hipStream_t stream)
 // 192 registers per lane, two workgroups per compute unit); more workgroups per compute unit: no difference
 constexpr uint32_t kSlideChunk = 192 * 1024;
 constexpr int kSlideVec = kSlideChunk / (kCopyThreads * 16);
-constexpr uint32_t kSlideSpinLimit = 1u << 22;      // polls of a microsecond or two each: seconds
 
 __global__ void slide_reset(uint32_t *progress, uint32_t n, uint32_t *failed)
 {
     for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) progress[i] = 0;
-    if (threadIdx.x == 0) *failed = 0;
+    if (failed && threadIdx.x == 0) *failed = 0;      // null: keep what an earlier launch of this plan reported
 }
 
 __global__ __launch_bounds__(kCopyThreads) void slide_down(char *dst, const char *src, uint64_t len,
@@ -192,7 +191,8 @@ __global__ __launch_bounds__(kCopyThreads) void slide_down(char *dst, const char
     }
 }
 
-static hipError_t launch_slide_down(char *dst, const char *src, uint64_t len, SlideState *st, hipStream_t stream)
+static hipError_t launch_slide_down(char *dst, const char *src, uint64_t len, SlideState *st, bool clear_failed,
+                                    hipStream_t stream)
 {
     if (!st || !st->progress) return hipErrorInvalidValue;
     const uint64_t chunks = (len + kSlideChunk - 1) / kSlideChunk;
@@ -207,11 +207,12 @@ static hipError_t launch_slide_down(char *dst, const char *src, uint64_t len, Sl
         st->max_grid = (uint32_t)std::min<int64_t>((int64_t)std::min(per_cu, 2) * cus, kSlideMaxGrid);
     }
     uint32_t grid = (uint32_t)std::min<uint64_t>(chunks, st->max_grid);
-    hipLaunchKernelGGL(slide_reset, dim3(1), dim3(256), 0, stream, st->progress, grid, st->failed);
+    hipLaunchKernelGGL(slide_reset, dim3(1), dim3(256), 0, stream, st->progress, grid,
+                       clear_failed ? st->failed : (uint32_t *)nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(slide_down, dim3(grid), dim3(kCopyThreads), 0, stream, dst, (const char *)src, len,
-                       st->progress, st->failed, kSlideSpinLimit);
+                       st->progress, st->failed, st->spin_limit);
     return hipGetLastError();
 }
 
@@ -237,6 +238,8 @@ hipError_t slide_state_failed(SlideState *st, hipStream_t stream, uint32_t *out)
     if (!st->progress) return hipSuccess;
     hipError_t e = hipMemcpyAsync(out, st->failed, 4, hipMemcpyDeviceToHost, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    // reported once: a later plan without an in-place move must not see it again
+    if (e == hipSuccess && *out) e = hipMemsetAsync(st->failed, 0, 4, stream);
     return e;
 }
 
@@ -251,6 +254,7 @@ hipError_t launch_slide(char *base, const uint64_t *src, const uint64_t *dst, co
 {
     std::vector<CopySeg> phase;
     uint64_t phase_first_src = 0;
+    bool first_slide = true;        // the plan's first in-place move clears the "gave up" flag, later ones keep it
     auto flush = [&]() -> hipError_t {
         if (phase.empty()) return hipSuccess;
         hipError_t e = launch_copy(phase.data(), (uint32_t)phase.size(), stream);
@@ -270,7 +274,9 @@ hipError_t launch_slide(char *base, const uint64_t *src, const uint64_t *dst, co
             continue;
         }
         if (hipError_t e = flush()) return e;
-        if (hipError_t e = launch_slide_down(base + dst[i], base + src[i], len[i], st, stream)) return e;
+        if (hipError_t e = launch_slide_down(base + dst[i], base + src[i], len[i], st, first_slide, stream))
+            return e;
+        first_slide = false;
         if (launches) *launches += 1;
     }
     return flush();

@@ -91,6 +91,7 @@ _PROTOS = {
     "salus_job_set_cost": [C.c_void_p, C.c_int32, C.c_uint64],
     "salus_fused_check": [C.c_void_p],
     "salus_fused_spin_limit": [C.c_void_p, C.c_uint32],
+    "salus_compact_spin_limit": [C.c_void_p, C.c_uint32],
     "salus_set_pending_many": [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_uint64), C.c_uint32],
     "salus_job_write": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
     "salus_job_read": [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_uint64],
@@ -209,6 +210,9 @@ class Pool:
 
     def fused_spin_limit(self, polls):
         return self._lib.salus_fused_spin_limit(self._h, polls)
+
+    def compact_spin_limit(self, polls):
+        return self._lib.salus_compact_spin_limit(self._h, polls)
 
     def set_pending_many(self, jobs_arr, n_arr, count):
         """jobs_arr: ctypes int32 array, n_arr: ctypes uint64 array."""

@@ -307,3 +307,24 @@ def test_compaction_direct_pieces_and_degenerate_small_free_space():
     assert dp.pool.compact() == o.compact() == [(4096, 0, C - 4096 - 512)]
     same_persistent_bytes(o, dp)
     dp.close()
+
+
+def test_in_place_move_that_gives_up_is_reported_and_every_workgroup_ends():
+    """The bounded wait of the in-place move, forced from the host: with a poll limit
+    of 0 a workgroup that finds its neighbour's chunk not yet read gives up (256
+    workgroups start together and each needs its left neighbour's chunk, so some
+    do), skips its write and runs on; the plan's second move must not hide what the
+    first one reported.  The pool is then destroyed; a fresh one compacts normally."""
+    GiB = 1 << 30
+    C = 2 * GiB + 64 * MiB
+    dp = DevicePool(C, max_lanes=1)
+    for s in (4096, GiB, 4096, GiB):
+        dp.pool.lane_alloc(s, 4096, 0, 1)
+    assert dp.pool.compact_spin_limit(0) == salus.OK
+    assert dp.pool.lane_free(0) == salus.OK and dp.pool.lane_free(2) == salus.OK
+    with pytest.raises(salus.SalusError) as err:
+        dp.pool.compact()
+    assert err.value.code == salus.EHIP and "gave up" in str(err.value)
+    torch.cuda.synchronize()                          # nothing is left running
+    dp.close()
+    test_forced_compaction_adversarial_shifts()
