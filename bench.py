@@ -510,9 +510,30 @@ def calibration_figures(torch, salus, stream, K=2048, N=2048, max_jobs=64, sets=
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         best = dt if best is None else min(best, dt)
-    out = {"workload": f"calibration: one {K} x {N} bf16 layer of J jobs per launch; 8 GiB plain copy",
+    out = {"workload": f"calibration: one {K} x {N} bf16 layer of J jobs per launch; 8 GiB plain copy; "
+                       "the LDS-tiled kernel's multiply without its memory traffic",
            "launches": rows, "copy_GBs_read_plus_write": round(2 * n / best / 1e9, 1)}
     log(f"[calibrate] copy {out['copy_GBs_read_plus_write']} GB/s read + write")
+    del cal
+    # what the matrix pipes sustain on nonzero operands, and at which clock
+    clk = torch.zeros(3, dtype=torch.int64, device="cuda:0")
+    out["mfma"] = []
+    for from_lds in (False, True):
+        salus.calibrate_mfma(clk.data_ptr(), 256, from_lds, stream)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        flop = salus.calibrate_mfma(clk.data_ptr(), 8192, from_lds, stream)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b)
+        cycles, ticks = (int(v) for v in clk[:2].tolist())
+        row = {"operands": "read from LDS every k-step, one barrier per slab" if from_lds else "held in registers",
+               "ms": round(ms, 3), "tflops": round(flop / (ms * 1e-3) / 1e12, 1),
+               "pct_of_bf16_mfma_peak": round(100 * flop / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 1),
+               "shader_clock_MHz": round(100.0 * cycles / max(ticks, 1))}
+        out["mfma"].append(row)
+        log(f"[calibrate] mfma {row}")
     return out
 
 

@@ -413,6 +413,17 @@ int32_t salus_check_pattern(const void *dev, uint64_t nbytes, uint64_t seed, voi
  * (src and dst are host pointers to K * N elements and must not overlap; N a
  * multiple of 128).  Pure data movement. */
 int32_t salus_pack_strip128(const uint16_t *src, uint16_t *dst, uint32_t K, uint32_t N);
+/* Calibration of the matrix pipes (measurement support, not part of the method):
+ * one workgroup of eight wavefronts per compute unit runs, `slabs` times, the 32
+ * v_mfma_f32_32x32x16_bf16 per wavefront that the LDS-tiled kernel issues for a
+ * 256 x 256 x 64 slab, on nonzero operands - on fragments held in registers
+ * (from_lds = 0) or read from LDS for every k-step with one barrier per slab
+ * (from_lds = 1) - and nothing else.  Asynchronous on `stream`; the caller times
+ * it.  dev_out: 24 device bytes, 8-aligned; receives {shader clock cycles, ticks
+ * of the 100 MHz wall clock} that one wavefront's loop took, so that the clock
+ * the chip holds under this load can be read off.  *flop (host, may be null):
+ * floating-point operations of the launch. */
+int32_t salus_calibrate_mfma(void *dev_out, uint32_t slabs, int32_t from_lds, void *stream, uint64_t *flop);
 /* Plain device copy with the library's copy kernel (memmove semantics when the
  * ranges overlap with dst < src). */
 int32_t salus_copy(void *dst, const void *src, uint64_t nbytes, void *stream);

@@ -896,6 +896,13 @@ int32_t salus_pack_strip128(const uint16_t *src, uint16_t *dst, uint32_t K, uint
     return SALUS_OK;
 }
 
+int32_t salus_calibrate_mfma(void *dev_out, uint32_t slabs, int32_t from_lds, void *stream, uint64_t *flop)
+{
+    if (!dev_out || !slabs || (uintptr_t)dev_out % 8) return SALUS_EINVAL;
+    return launch_mfma_rate((uint64_t *)dev_out, slabs, from_lds != 0, (hipStream_t)stream, flop) == hipSuccess
+               ? SALUS_OK : SALUS_EHIP;
+}
+
 int32_t salus_copy(void *dst, const void *src, uint64_t nbytes, void *stream)
 {
     if (!dst || !src || nbytes % 16 || (uintptr_t)dst % 16 || (uintptr_t)src % 16) return SALUS_EINVAL;

@@ -74,6 +74,8 @@ bool tiled_shape_ok(const Problem &p);
 uint64_t tiled_tiles(const Problem &p);
 hipError_t launch_grouped_bf16_tiled(const Problem *p, uint32_t n, hipStream_t stream,
                                      uint64_t *launches);
+// Calibration: the tiled kernel's multiply without its memory traffic (see kernels_gemm_tiled.hip).
+hipError_t launch_mfma_rate(uint64_t *dev_out, uint32_t slabs, bool lds, hipStream_t stream, uint64_t *flop);
 hipError_t launch_grouped_f32(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches);
 
 // ---- depth-fused forward ------------------------------------------------------

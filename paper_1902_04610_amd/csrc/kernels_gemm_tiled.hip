@@ -370,6 +370,88 @@ static hipError_t launch_tiled(Kernel kernel, int threads, const std::vector<Pro
     return hipSuccess;
 }
 
+// ---------------------------------------------------------------------------
+// Calibration: the multiply of grouped_dense_bf16_tiled<256> without its memory
+// traffic.  One workgroup of eight wavefronts per CU runs `slabs` times the 32
+// MFMAs per wavefront of a 256 x 256 x 64 slab, either on fragments read once
+// (lds == 0: what the matrix pipes sustain) or on fragments read from LDS for
+// every k-step with one barrier per slab (lds != 0: the tiled kernel's multiply
+// and LDS reads, nothing else).  Operands are nonzero (a pattern of small
+// integers and fractions): the clock a matrix-bound kernel runs at depends on
+// what the multipliers toggle.  Wavefront 0 of workgroup 0 reports the shader
+// clocks and the 100 MHz ticks its loop took, so the clock under this load can
+// be read off: out[0] = s_memtime difference, out[1] = wall-clock difference.
+template <bool LDS>
+__global__ __launch_bounds__(kThreads2) void mfma_rate(uint64_t *out, uint32_t slabs)
+{
+    constexpr int BM = 256, FN = 4;
+    __shared__ __attribute__((aligned(128))) unsigned char smem[2 * (BM + kBN) * kLine];
+    for (uint32_t i = threadIdx.x; i < 2 * (BM + kBN) * kLine / 4; i += kThreads2) {
+        const float a = 0.0625f * (float)((i * 7u) & 63u) - 2.0f, b = 0.03125f * (float)((i * 13u) & 127u) - 2.0f;
+        ((uint32_t *)smem)[i] = bf16_pack(a, b);
+    }
+    __syncthreads();
+    const uint32_t t = threadIdx.x, lane = t & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const uint32_t wm = wave >> 1, wn = wave & 1u;
+    const uint32_t fl = lane & 31u, fh = lane >> 5, fs = swz(fl);
+    const uint32_t afrag = (wm * 64u + fl) * kLine, bfrag = (BM + wn * 128u + fl) * kLine;
+    f32x16 acc[2][FN];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    bf16x8 av[2], bv[FN];
+    auto read = [&](const unsigned char *base, uint32_t ks) {
+        const uint32_t off = ((2u * ks + fh) ^ fs) << 4, off_odd = off ^ 64u;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) av[i] = *(const bf16x8 *)(base + afrag + 32 * i * kLine + (i & 1 ? off_odd : off));
+#pragma unroll
+        for (int j = 0; j < FN; ++j) bv[j] = *(const bf16x8 *)(base + bfrag + 32 * j * kLine + (j & 1 ? off_odd : off));
+    };
+    if (!LDS) read(smem, 0);
+    const uint64_t c0 = __builtin_readcyclecounter(), w0 = wall_clock64();
+    uint32_t stage = 0;
+    for (uint32_t s = 0; s < slabs; ++s) {
+#pragma unroll
+        for (uint32_t ks = 0; ks < 4; ++ks) {
+            if (LDS) read(smem + stage, ks);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+        if (LDS) __syncthreads();
+        stage ^= (BM + kBN) * kLine;
+    }
+    const uint64_t c1 = __builtin_readcyclecounter(), w1 = wall_clock64();
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += acc[i][j][r];
+    if (blockIdx.x == 0 && t == 0) {
+        out[0] = c1 - c0;
+        out[1] = w1 - w0;
+    }
+    if (sum == 1.2345f) out[2] = 1;        // keeps the multiplies
+}
+
+// flop: what the launch computes (2 * 256 * 256 * 64 per slab and workgroup)
+hipError_t launch_mfma_rate(uint64_t *dev_out, uint32_t slabs, bool lds, hipStream_t stream, uint64_t *flop)
+{
+    const uint32_t grid = resident_grid();
+    if (lds) hipLaunchKernelGGL(mfma_rate<true>, dim3(grid), dim3(kThreads2), 0, stream, dev_out, slabs);
+    else hipLaunchKernelGGL(mfma_rate<false>, dim3(grid), dim3(kThreads2), 0, stream, dev_out, slabs);
+    if (flop) *flop = 2ull * 256 * 256 * 64 * slabs * grid;
+    return hipGetLastError();
+}
+
 hipError_t launch_grouped_bf16_tiled(const Problem *p, uint32_t n, hipStream_t stream, uint64_t *launches)
 {
     std::vector<Problem> big, small;

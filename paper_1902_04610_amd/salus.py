@@ -118,6 +118,7 @@ _PROTOS = {
     "salus_check_pattern": [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.POINTER(C.c_uint64),
                             C.c_void_p],
     "salus_copy": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p],
+    "salus_calibrate_mfma": [C.c_void_p, C.c_uint32, C.c_int32, C.c_void_p, C.POINTER(C.c_uint64)],
     "salus_pack_strip128": [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32],
 }
 
@@ -383,3 +384,12 @@ def copy(dst_ptr, src_ptr, nbytes, stream=None):
     rc = lib().salus_copy(dst_ptr, src_ptr, nbytes, stream)
     if rc != OK:
         raise SalusError(rc, "salus_copy")
+
+
+def calibrate_mfma(dev_out_ptr, slabs, from_lds, stream=None):
+    """Launches the matrix-pipe calibration kernel; returns the launch's flop count."""
+    flop = C.c_uint64()
+    rc = lib().salus_calibrate_mfma(dev_out_ptr, slabs, 1 if from_lds else 0, stream, C.byref(flop))
+    if rc != OK:
+        raise SalusError(rc, "salus_calibrate_mfma")
+    return flop.value
