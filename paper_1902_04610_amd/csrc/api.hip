@@ -914,9 +914,12 @@ int32_t salus_copy(void *dst, const void *src, uint64_t nbytes, void *stream)
         CopySeg seg{src, dst, nbytes};
         e = launch_copy(&seg, 1, s);
     } else if (dp < sp) {
-        // this self-check has no pool: its in-place moves share one process-wide set of
-        // counters, so overlapping calls of salus_copy must not run concurrently
-        static SlideState state;
+        // this self-check has no pool: its in-place moves share one set of counters per device
+        // (kept until the process ends), so overlapping calls of salus_copy must not run concurrently
+        static SlideState states[kMaxDevices];
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SALUS_EHIP;
+        SlideState &state = states[dev];
         if (!state.progress && slide_state_create(&state) != hipSuccess) return SALUS_EHIP;
         uint64_t so = (uint64_t)(sp - dp), zo = 0, len = nbytes;   // offsets relative to dst
         e = launch_slide(dp, &so, &zo, &len, 1, &state, s, nullptr);
