@@ -295,6 +295,22 @@ def test_bf16_gelu_inputs_of_small_magnitude():
         assert np.abs(r).max() < 2e-3 and norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
 
 
+def test_bf16_gelu_in_the_negative_tail():
+    """Pre-activations that are all in [-6, -3.5]: every output is below 1e-3 in magnitude
+    and the kernels' approximation of the normal tail, whose error is absolute (3e-7), is
+    what decides the comparison.  It stays inside the bf16 bound relative to the largest
+    output of the matrix (|z| * 3e-7 against 3.5 * 2.3e-4)."""
+    jobs = [dict(M=33, dims=(128, 264), acts=[GELU], x_lo=0.9, x_hi=1.0, w_scale=0.5, w_mean=-5.0),
+            dict(M=16, dims=(64, 64), acts=[GELU], x_lo=0.99, x_hi=1.0, w_scale=0.05, w_mean=-4.0),
+            dict(M=200, dims=(128, 264), acts=[GELU], x_lo=0.9, x_hi=1.0, w_scale=0.5, w_mean=-5.0)]
+    outs, refs, launches = run_jobs(jobs, salus.BF16)
+    for o, r, j in zip(outs, refs, jobs):
+        e = norm_rel_err(o, r)
+        print("bf16 GELU tail", j["M"], "largest |ref|", np.abs(r).max(), "error", e)
+        assert np.isfinite(o).all() and (r <= 0).all() and np.abs(r).max() < 2e-3, j
+        assert e < TOL_BF16, (j, e)
+
+
 def test_special_weights_bf16():
     """W = I copies the input, a single one at (k, n) moves column k to column n:
     catches a transposed or permuted operand independently of the oracle's GEMM."""
