@@ -31,6 +31,17 @@ __global__ __launch_bounds__(kGemmThreads) void grouped_dense_bf16(GroupArgs a)
     else dense_bf16_tile<MT, TW, NT>(p, tile, lds);
 }
 
+// 64-row tiles of 128 columns for deep layers of jobs with 33 .. 128 rows: every weight passes through a
+// compute unit once.  Two workgroups per compute unit (registers capped accordingly), so that one
+// workgroup's reduction and epilogue overlap the other's stream.
+template <bool NT>
+__global__ __launch_bounds__(kGemmThreads, 2) void grouped_dense_bf16_rows64(GroupArgs a)
+{
+    __shared__ float lds[reduce_lds_floats<32>()];
+    const Tile tile = find_tile<64, 128>(a);
+    dense_bf16_tile<4, false, NT>(a.p[tile.problem], tile, lds);
+}
+
 // Jobs of 33 .. 128 rows that do not go to the LDS-tiled kernel: row tiles of 64
 // rows, 64 columns wide (see dense_tile_n64.hpp).
 template <bool TW, bool NT>
@@ -86,6 +97,7 @@ static hipError_t launch_groups(const Problem *p, uint32_t n, uint32_t tn, uint3
 constexpr uint32_t kTiledAlways = 128, kTiledMaybe = 65;
 constexpr uint64_t kTiledMinGrid = 256;
 constexpr uint64_t kFullGrid = 256;      // one workgroup per compute unit
+constexpr uint32_t kDeepK = 1024;
 
 hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipStream_t stream,
                                uint64_t *launches)
@@ -113,12 +125,15 @@ hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipSt
     // workgroups, and the weights pass through a compute unit's memory path once per
     // 64 rows (2048 x 2048 layers of 8 jobs at 64 rows: 21.0 us against 22.7 us
     // forward, 21.4 against 28.2 us for the input gradient, whose rows are then read
-    // in whole cache lines).  With enough jobs to fill the chip, and above 128 rows,
-    // 32-row tiles of 128 columns as before: there the 64-row variants lose (64 jobs
-    // of 2048 x 2048 at 64 rows: 137 us with two 32-row tiles, 123 us with one
-    // 64 x 128 tile, 142 us with 64 x 64 tiles; but on the 1024-deep layers of the
-    // inference models the 64 x 128 tile, at one workgroup per compute unit, was 5 %
-    // slower than two 32-row tiles, which overlap each other's start and end).
+    // in whole cache lines).  With enough jobs to fill the chip: layers at least 1024 deep
+    // get one 64-row tile of 128 columns per workgroup, so that every weight passes through
+    // a compute unit once, with registers capped for two workgroups per compute unit (64
+    // models of the inference workload at 48 / 64 rows: 0.250 / 0.270 ms per round against
+    // 0.287 / 0.300 ms with two 32-row tiles, the second of which reads the weights from L2;
+    // the same 64-row tile uncapped, one workgroup per compute unit, had been 5 % slower
+    // than the two 32-row tiles on 1024-deep layers: nothing then overlaps a workgroup's
+    // reduction and epilogue); shallower layers, transposed weights and jobs above 128 rows
+    // keep 32-row tiles of 128 columns.
     std::vector<Problem> small, mid, large;
     for (uint32_t i = 0; i < n; ++i)
         (p[i].M <= 32 ? small : p[i].M <= 128 ? mid : large).push_back(p[i]);
@@ -133,6 +148,11 @@ hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipSt
             else if (one_row_tile) hipLaunchKernelGGL((grouped_dense_bf16<MT_, false, true>), grid, block, 0, stream, a);       \
             else hipLaunchKernelGGL((grouped_dense_bf16<MT_, false, false>), grid, block, 0, stream, a);                        \
         } while (0)
+        if (mt == 4) {      // forward only (the launcher never asks for it with transposed weights)
+            if (one_row_tile) hipLaunchKernelGGL((grouped_dense_bf16_rows64<true>), grid, block, 0, stream, a);
+            else hipLaunchKernelGGL((grouped_dense_bf16_rows64<false>), grid, block, 0, stream, a);
+            return;
+        }
         if (mt == 1) SALUS_WIDE(1);
         else SALUS_WIDE(2);
 #undef SALUS_WIDE
@@ -151,9 +171,17 @@ hipError_t launch_grouped_bf16(const Problem *p, uint32_t n, bool trans_w, hipSt
     if (!mid.empty()) {
         uint64_t wide_tiles = 0;
         for (const Problem &q : mid) wide_tiles += (uint64_t)((q.M + 63) / 64) * ((q.N + 127) / 128);
-        hipError_t e = wide_tiles >= kFullGrid
-                           ? launch_groups(mid.data(), (uint32_t)mid.size(), 128, 0, 0, launch_wide, launches, 2)
-                           : launch_groups(mid.data(), (uint32_t)mid.size(), 64, 0, 0, launch_n64, launches, 4);
+        hipError_t e = hipSuccess;
+        if (wide_tiles < kFullGrid) {
+            e = launch_groups(mid.data(), (uint32_t)mid.size(), 64, 0, 0, launch_n64, launches, 4);
+        } else {
+            std::vector<Problem> deep, shallow;
+            for (const Problem &q : mid) (!trans_w && q.K >= kDeepK ? deep : shallow).push_back(q);
+            if (!shallow.empty())
+                e = launch_groups(shallow.data(), (uint32_t)shallow.size(), 128, 0, 0, launch_wide, launches, 2);
+            if (e == hipSuccess && !deep.empty())
+                e = launch_groups(deep.data(), (uint32_t)deep.size(), 128, 0, 0, launch_wide, launches, 4);
+        }
         if (e != hipSuccess) return e;
     }
     if (!large.empty())

@@ -174,6 +174,28 @@ def test_bf16_rows_33_to_128_take_64_row_tiles_of_either_width(M):
         assert np.isfinite(o).all() and norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
 
 
+def test_bf16_deep_layers_of_many_mid_sized_jobs_take_one_64_row_tile():
+    """Enough jobs to fill the chip and layers at least 1024 deep: 64-row tiles of 128
+    columns (one per job up to 64 rows, two above, the second reading the weights
+    from L2); ragged K and N, strips, and a round that mixes them with shallow layers."""
+    deep = [dict(M=[33, 48, 64, 40][i % 4], dims=(1032, 904), acts=[[GELU, RELU, NONE][i % 3]]) for i in range(30)]
+    deep += [dict(M=[64, 57][i % 2], dims=(1024, 1024), acts=[GELU], strip=True) for i in range(6)]
+    outs, refs, launches = run_jobs(deep, salus.BF16)            # 30 x 8 + 6 x 8 column tiles >= 256
+    assert launches == 1
+    for o, r, j in zip(outs, refs, deep):
+        assert np.isfinite(o).all() and norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
+    two_tiles = [dict(M=[65, 100, 128, 127][i % 4], dims=(1032, 520), acts=[[RELU, GELU][i % 2]]) for i in range(30)]
+    outs, refs, launches = run_jobs(two_tiles, salus.BF16)       # K is no multiple of 64: not for the LDS-tiled kernel
+    assert launches == 1
+    for o, r, j in zip(outs, refs, two_tiles):
+        assert np.isfinite(o).all() and norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
+    mixed = deep[:32] + [dict(M=50, dims=(40, 1000), acts=[RELU]) for i in range(8)]
+    outs, refs, launches = run_jobs(mixed, salus.BF16)
+    assert launches == 2                                          # deep and shallow layers of the same depth
+    for o, r, j in zip(outs, refs, mixed):
+        assert np.isfinite(o).all() and norm_rel_err(o, r) < TOL_BF16_TIGHT, (j, norm_rel_err(o, r))
+
+
 def test_bf16_mixed_batch_sizes_and_depths_in_one_packed_iteration():
     jobs = [dict(M=m, dims=(256, 1024, 256, 264), acts=[GELU, GELU, NONE]) for m in (1, 7, 16, 23, 32)]
     jobs += [dict(M=9, dims=(128, 136), acts=[RELU]), dict(M=32, dims=(64, 64, 64, 64, 64), acts=[RELU] * 3 + [NONE])]
