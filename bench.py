@@ -534,6 +534,28 @@ def calibration_figures(torch, salus, stream, K=2048, N=2048, max_jobs=64, sets=
                "shader_clock_MHz": round(100.0 * cycles / max(ticks, 1))}
         out["mfma"].append(row)
         log(f"[calibrate] mfma {row}")
+    # the vendor library on the sweep's largest point: 64 independent products of the three layer
+    # shapes at 4096 rows (torch.bmm, bf16 in, bf16 out, no activation) - a yardstick, not the product
+    out["vendor_bmm"] = []
+    rows_ = 4096
+    for K, N in zip(DIMS[:-1], DIMS[1:]):
+        xa = torch.randn(MODELS, rows_, K, device="cuda:0").to(torch.bfloat16)
+        wa = (torch.randn(MODELS, K, N, device="cuda:0") * 0.02).to(torch.bfloat16)
+        for _ in range(2):
+            torch.bmm(xa, wa)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            torch.bmm(xa, wa)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / 5
+        row = {"K": K, "N": N, "rows": rows_, "ms": round(ms, 3),
+               "tflops": round(2.0 * MODELS * rows_ * K * N / (ms * 1e-3) / 1e12, 1)}
+        out["vendor_bmm"].append(row)
+        log(f"[calibrate] vendor bmm {row}")
+        del xa, wa
     return out
 
 
