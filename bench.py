@@ -514,6 +514,18 @@ def calibration_figures(torch, salus, stream, K=2048, N=2048, max_jobs=64, sets=
                        "the LDS-tiled kernel's multiply without its memory traffic",
            "launches": rows, "copy_GBs_read_plus_write": round(2 * n / best / 1e9, 1)}
     log(f"[calibrate] copy {out['copy_GBs_read_plus_write']} GB/s read + write")
+    # a kernel that only loads: what the read path delivers to a pure stream
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
+    salus.calibrate_read(cal.data_ptr(), n, sink.data_ptr(), stream)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(5):
+        salus.calibrate_read(cal.data_ptr(), n, sink.data_ptr(), stream)
+    b.record()
+    torch.cuda.synchronize()
+    out["read_only_GBs"] = round(5 * n / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
+    log(f"[calibrate] load-only kernel over 8 GiB: {out['read_only_GBs']} GB/s")
     del cal
     # what the matrix pipes sustain on nonzero operands, and at which clock
     clk = torch.zeros(3, dtype=torch.int64, device="cuda:0")

@@ -424,6 +424,13 @@ int32_t salus_pack_strip128(const uint16_t *src, uint16_t *dst, uint32_t K, uint
  * the chip holds under this load can be read off.  *flop (host, may be null):
  * floating-point operations of the launch. */
 int32_t salus_calibrate_mfma(void *dev_out, uint32_t slabs, int32_t from_lds, void *stream, uint64_t *flop);
+/* Calibration of the read path (measurement support): a kernel that only loads.
+ * It reads [dev, dev + nbytes) once - 256 KiB in one piece per workgroup, 16
+ * bytes per lane, eight loads in flight per wavefront, non-temporal - and writes
+ * nothing (dev_sink: 16 device bytes, 16-aligned, written only if the data xor
+ * to one particular value).  nbytes a multiple of 4096, dev 16-aligned.
+ * Asynchronous on `stream`; the caller times it. */
+int32_t salus_calibrate_read(const void *dev, uint64_t nbytes, void *dev_sink, void *stream);
 /* Plain device copy with the library's copy kernel (memmove semantics when the
  * ranges overlap with dst < src). */
 int32_t salus_copy(void *dst, const void *src, uint64_t nbytes, void *stream);

@@ -896,6 +896,12 @@ int32_t salus_pack_strip128(const uint16_t *src, uint16_t *dst, uint32_t K, uint
     return SALUS_OK;
 }
 
+int32_t salus_calibrate_read(const void *dev, uint64_t nbytes, void *dev_sink, void *stream)
+{
+    if (!dev || !dev_sink || nbytes % 4096 || (uintptr_t)dev % 16 || (uintptr_t)dev_sink % 16) return SALUS_EINVAL;
+    return launch_read_only(dev, nbytes, dev_sink, (hipStream_t)stream) == hipSuccess ? SALUS_OK : SALUS_EHIP;
+}
+
 int32_t salus_calibrate_mfma(void *dev_out, uint32_t slabs, int32_t from_lds, void *stream, uint64_t *flop)
 {
     if (!dev_out || !slabs || (uintptr_t)dev_out % 8) return SALUS_EINVAL;

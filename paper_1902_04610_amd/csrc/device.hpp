@@ -40,6 +40,8 @@ hipError_t launch_slide(char *base, const uint64_t *src, const uint64_t *dst, co
 
 hipError_t launch_scan_u64(const uint64_t *dev_in, uint32_t n, uint64_t *dev_out, hipStream_t s);
 hipError_t launch_fill_pattern(void *dev, uint64_t nbytes, uint64_t seed, hipStream_t s);
+// Calibration: a kernel that only loads (nbytes a multiple of 4096, sink 16 device bytes).
+hipError_t launch_read_only(const void *dev, uint64_t nbytes, void *sink, hipStream_t s);
 hipError_t launch_check_pattern(const void *dev, uint64_t nbytes, uint64_t seed,
                                 unsigned long long *dev_bad, hipStream_t s);
 

@@ -331,6 +331,41 @@ __global__ __launch_bounds__(256) void check_pattern(const uint64_t *p, uint64_t
     if (mine) atomicAdd(bad, mine);
 }
 
+// Calibration: nothing but loads.  Every workgroup reads 256 KiB in one piece, a wavefront
+// instruction 1 KiB, eight instructions in flight per wavefront, non-temporal: what the
+// memory system delivers to a kernel that only streams (sink is written only if the data
+// xor to a value they never have).
+__global__ __launch_bounds__(256) void read_only(const char *base, uint64_t nbytes, u32x4 *sink)
+{
+    constexpr uint64_t kPiece = 256 * 1024;
+    const uint64_t off = (uint64_t)blockIdx.x * kPiece;
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint64_t left = nbytes - off;
+    const uint32_t n = (uint32_t)((left < kPiece ? left : kPiece) / 4096);      // whole 4 KiB steps of the workgroup
+    const char *p = base + off + wave * 1024 + lane * 16;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    uint32_t i = 0;
+    for (; i + 8 <= n; i += 8) {
+        u32x4 v[8];
+#pragma unroll
+        for (int d = 0; d < 8; ++d) v[d] = __builtin_nontemporal_load((const u32x4 *)(p + (uint64_t)(i + d) * 4096));
+#pragma unroll
+        for (int d = 0; d < 8; ++d) acc ^= v[d];
+    }
+    for (; i < n; ++i) acc ^= __builtin_nontemporal_load((const u32x4 *)(p + (uint64_t)i * 4096));
+    if (acc[0] == 0x9e3779b9u && acc[1] == 0x7f4a7c15u && acc[2] == 0xf39cc060u && acc[3] == 0x5cedc834u) *sink = acc;
+}
+
+// nbytes: a multiple of 4096; sink: 16 device bytes
+hipError_t launch_read_only(const void *dev, uint64_t nbytes, void *sink, hipStream_t s)
+{
+    const uint64_t pieces = (nbytes + 256 * 1024 - 1) / (256 * 1024);
+    if (!pieces) return hipSuccess;
+    if (pieces > 0x7fffffffull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(read_only, dim3((uint32_t)pieces), dim3(256), 0, s, (const char *)dev, nbytes, (u32x4 *)sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_fill_pattern(void *dev, uint64_t nbytes, uint64_t seed, hipStream_t s)
 {
     const uint64_t nwords = nbytes / 8;

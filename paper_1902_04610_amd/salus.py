@@ -119,6 +119,7 @@ _PROTOS = {
                             C.c_void_p],
     "salus_copy": [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p],
     "salus_calibrate_mfma": [C.c_void_p, C.c_uint32, C.c_int32, C.c_void_p, C.POINTER(C.c_uint64)],
+    "salus_calibrate_read": [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p],
     "salus_pack_strip128": [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32],
 }
 
@@ -393,3 +394,10 @@ def calibrate_mfma(dev_out_ptr, slabs, from_lds, stream=None):
     if rc != OK:
         raise SalusError(rc, "salus_calibrate_mfma")
     return flop.value
+
+
+def calibrate_read(dev_ptr, nbytes, sink_ptr, stream=None):
+    """Launches the load-only calibration kernel over [dev_ptr, dev_ptr + nbytes)."""
+    rc = lib().salus_calibrate_read(dev_ptr, nbytes, sink_ptr, stream)
+    if rc != OK:
+        raise SalusError(rc, "salus_calibrate_read")
